@@ -1,0 +1,172 @@
+/*
+ * xq.h -- C ABI of the MI355X (gfx950) quantized-KV decode library.
+ *
+ * The library implements the data-parallel hot path of XQuant (arXiv 2510.11236):
+ *   - quantize + bit-pack the K/V cache at 1 or 2 bits with asymmetric min/max
+ *     group quantization (Sec. 3.1, Eq. 1-2), the data-free calibration of the
+ *     stored zero-point and scale (Sec. 3.2, Eq. 12) and cross-layer sharing of
+ *     the integer codes between the two layers of a pair, each layer keeping its
+ *     own scale and zero-point (Sec. 3.3.3, accelerated form Sec. 3.3.4);
+ *   - keys grouped per channel (g consecutive tokens of one channel), values per
+ *     token (g consecutive channels of one token), the newest tokens kept in fp16
+ *     (Sec. 4.1 "Baselines and Implementations": group size 32, residual 128);
+ *   - decode attention that dequantizes X^ = X_Q * s^ + z^ (Sec. 3.2, 3.3.3) in
+ *     registers inside q.K^T -> softmax -> .V.
+ *
+ * Conventions
+ *   - Every "device" pointer is HIP device memory owned by the caller.  The
+ *     library never allocates or frees device memory.  "host" pointers are
+ *     ordinary process memory.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Kernels are enqueued on it and the call returns without waiting.  Length
+ *     bookkeeping in the host handle advances at call time, so calls on one
+ *     handle must be issued in program order from one thread at a time.
+ *   - fp16 = IEEE binary16.  Inputs must be finite.
+ *   - All sequences of a batch have the same length.
+ *   - Return value: 0 (XQ_OK) or a negative XQ_ERR_* code; nothing is enqueued
+ *     when an error is returned, except XQ_ERR_HIP (launch failure).
+ *
+ * Split rule (one policy for keys and values).  With T tokens in a layer's
+ * cache, T_q = g * ceil(max(T - R, 0) / g) tokens are held as packed codes and
+ * the newest r = T - T_q tokens (R - g < r <= R once T >= R) stay in an fp16
+ * ring of R slots, token t in slot t mod R.  An append that finds r == R first
+ * moves the oldest g ring tokens into packed form.
+ *
+ * Arithmetic contract (what makes the stored bytes unique).  Per group, in
+ * fp32, one correctly rounded operation per step, no fused multiply-add:
+ *   mn, mx = min, max of the g fp16 values;  n = 2^B - 1
+ *   s  = (mx - mn) / n            (s = 0 when mx == mn)
+ *   c  = clamp(rint((x - mn) / s), 0, n), ties to even; c = 0 when s == 0
+ *   z^ = mn + (eta_B * n) * s ,  s^ = (1 - 2 eta_B) * s        (Eq. 12)
+ * with eta_B * n and 1 - 2 eta_B formed in fp32 on the host.  s^ and z^ are
+ * stored as fp16 (round to nearest even).  A layer that takes its codes from
+ * the layer below computes and stores only s^ and z^ of its own data.
+ *
+ * Packed layout (part of the contract; all regions are per layer, then
+ * [batch][kv head], 256-byte aligned, capacity max_tokens):
+ *   K codes  tokens in blocks of 32.  A token's code row has W = D*B/32 words;
+ *            channel d is in row word d / (32/B) at bit B * (d mod (32/B)).
+ *            A block stores rows in chunks of CW = min(4, W) words:
+ *            word address in block = chunk*32*CW + (t mod 32)*CW + (word mod CW),
+ *            chunk = word / CW.  Block b starts at word b*32*W.
+ *   V codes  tokens in blocks of 32.  Channel d belongs to slot d / CPL,
+ *            CPL = D/64.  Per block a slot holds the 32*CPL codes ordered
+ *            e = (t mod 32)*CPL + (d mod CPL), B bits each, LSB first, in
+ *            WS = CPL*B words: word (e*B)/32, bit (e*B) mod 32.  A block is
+ *            [slot 0..63][WS words]; block b starts at word b*64*WS.
+ *   K meta   [token group t/g][channel d] of 4 bytes: low half s^, high half z^.
+ *   V meta   [token t][channel group d/g] of 4 bytes, same halves.
+ *   residual [slot t mod R][D] fp16, for K and for V.
+ * Only layers that store codes have code regions.
+ */
+#ifndef XQ_H
+#define XQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define XQ_OK 0
+#define XQ_ERR_INVALID_ARG (-1)  /* null pointer, bad shape, eta outside [0, 0.5), bad layer range */
+#define XQ_ERR_UNSUPPORTED (-2)  /* head_dim / group / GQA ratio the kernels are not built for */
+#define XQ_ERR_CAPACITY    (-3)  /* more than max_tokens, arena or workspace too small */
+#define XQ_ERR_STATE       (-4)  /* pack on a non-empty layer, decode or unpack on an empty one */
+#define XQ_ERR_HIP         (-5)  /* a HIP call or kernel launch failed */
+
+/* Method parameters (Appendix Alg. 1 inputs kq, vq, km, vm, eta[2]; Sec. 4.1 group
+ * size and residual length) and tensor shape. */
+typedef struct xq_config {
+    int32_t n_layers;    /* L >= 1 */
+    int32_t batch;       /* b >= 1 */
+    int32_t n_q_heads;   /* multiple of n_kv_heads; ratio in {1, 2, 4} (1 when head_dim is 64) */
+    int32_t n_kv_heads;
+    int32_t head_dim;    /* D: 64 or 128 */
+    int32_t group;       /* g: 32 or 64, g <= D */
+    int32_t residual;    /* R: multiple of g, g <= R <= 1024 */
+    int32_t max_tokens;  /* capacity per sequence */
+    int32_t kq, vq;      /* layers [0, kq) hold 2-bit key codes, the others 1-bit; vq likewise for values */
+    int32_t km, vm;      /* layers >= km (vm): the odd layer of each pair reuses the codes of the layer below */
+    float eta1, eta2;    /* calibration parameter for 1-bit / 2-bit groups, in [0, 0.5) */
+} xq_config;
+
+typedef struct xq_cache xq_cache; /* opaque host handle */
+
+/* Sizes the caller must provide.  arena_bytes: device memory for the whole cache.
+ * workspace_bytes: device scratch for one xq_decode_attention call over all layers
+ * at max_tokens.  Host pointers.  XQ_ERR_INVALID_ARG / XQ_ERR_UNSUPPORTED on a bad config
+ * (including a shared pair whose two layers would have different bit widths). */
+int xq_cache_bytes(const xq_config *cfg, size_t *arena_bytes, size_t *workspace_bytes);
+
+/* Creates the host handle over a caller-owned device arena (256-byte aligned, at least
+ * arena_bytes).  The arena needs no initialisation.  *out is freed with xq_cache_destroy;
+ * the arena stays the caller's. */
+int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, xq_cache **out);
+void xq_cache_destroy(xq_cache *cache);
+
+/* Sets every layer's length to 0 (host bookkeeping only). */
+int xq_cache_reset(xq_cache *cache);
+
+/* Tokens held by a layer: total T and packed T_q (host pointers, either may be NULL). */
+int xq_cache_len(const xq_cache *cache, int32_t layer, int32_t *T, int32_t *T_q);
+
+/* Prefill: quantize and pack T tokens of layers [layer0, layer0 + n_layers)
+ * (Appendix Alg. 1, first loop: Quantize, or PseudoQuantize for a layer that shares).
+ * k_f16, v_f16: device fp16, element (l, i, h, t, d) at
+ *   base + l*strides[0] + i*strides[1] + h*strides[2] + t*strides[3] + d   (in elements),
+ * l relative to layer0.  The layers must be empty (XQ_ERR_STATE otherwise); T <= max_tokens.
+ * Writes codes (code-storing layers), metadata and the fp16 ring; sets the lengths to T. */
+int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
+                     const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream);
+
+/* Decode-time append of one token per sequence to layers [layer0, layer0 + n_layers).
+ * k_new_f16, v_new_f16: device fp16 [n_layers][batch][n_kv_heads][D], contiguous.
+ * A layer whose ring is full first has its oldest g tokens quantized and packed (same
+ * arithmetic as xq_quantize_pack, so prefill(T) + n appends == prefill(T + n) bit for bit).
+ * XQ_ERR_CAPACITY when a layer already holds max_tokens. */
+int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_new_f16,
+                    const void *v_new_f16, void *hip_stream);
+
+/* Decode attention for layers [layer0, layer0 + n_layers): one query per (layer, sequence,
+ * query head) against every token the layer holds (Appendix Alg. 1, second loop: codes of
+ * the layer that stores them, scale and zero-point of the layer itself; then
+ * softmax(sm_scale * q K^T) V).  Query head hq reads kv head hq / (n_q_heads / n_kv_heads).
+ * q_f16: device fp16 [n_layers][batch][n_q_heads][D]; out_f32: device fp32, same shape.
+ * dev_workspace: device scratch, at least the size xq_cache_bytes reported (less is accepted
+ * when it suffices for the current lengths).  flags: 0, or XQ_DECODE_PAIR_FUSED to let one
+ * workgroup serve both layers of a sharing pair so that their common codes are fetched once
+ * (the result is the same up to fp32 summation order).  All layers in the range must hold
+ * the same, non-zero number of tokens. */
+#define XQ_DECODE_PAIR_FUSED 1
+int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
+                        void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
+                        int32_t flags, void *hip_stream);
+
+/* Test/debug: expands a layer's stored codes to one byte per element,
+ * dev_codes_u8: device [batch][n_kv_heads][T_q][D].  XQ_ERR_STATE if the layer stores none. */
+int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t *dev_codes_u8,
+                    void *hip_stream);
+
+/* Byte offsets of a layer's regions inside the arena (host pointer to 6 values:
+ * k_codes, v_codes, k_meta, v_meta, k_residual, v_residual; a code offset is -1 for a layer
+ * that stores none) and, in sizes[6], the bytes of each region per (batch, kv head). */
+int xq_cache_layout(const xq_cache *cache, int32_t layer, int64_t offsets[6], int64_t sizes[6]);
+
+/* Test/tuning hook: forces the number of 128-token tiles per packed-token split used by
+ * xq_decode_attention (0 restores the automatic plan).  Results must not depend on it beyond
+ * fp32 summation order. */
+void xq_debug_set_tiles_per_split(xq_cache *cache, int32_t tiles_per_split);
+
+/* Equivalent bit-width (Appendix C): stored code bits per element averaged over layers and
+ * over keys and values.  include_metadata = 0: the paper's figure (codes only).
+ * include_metadata = 1: adds the fp16 scale/zero and the fp16 ring at T tokens per sequence. */
+double xq_equivalent_bits(const xq_config *cfg, int32_t include_metadata, int32_t T);
+
+const char *xq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XQ_H */

@@ -1,0 +1,493 @@
+// Split-K decode attention over the packed cache, gfx950.
+//
+// Dequantization X^ = X_Q * s^ + z^ (Sec. 3.2 / 3.3.3) never materialises: scale and
+// zero-point are folded into the operand that is uniform over a group,
+//   keys    score_t = sum_d (q_d s^_{G,d}) c_{t,d} + sum_d q_d z^_{G,d}      (per token group G)
+//   values  o_d     = sum_t (p_t s^_{t,j}) c_{t,d} + sum_t p_t z^_{t,j}      (j = channel group of d)
+// so the inner loops touch each code once: one AND isolates a pair of codes in the two
+// halves of a register, where each half is read as an fp16 subnormal c * 2^(shift-24)
+// (the power of two is undone exactly in the uniform operand), and one FMA per code
+// (keys: fp32 weight x fp16 code, v_fma_mix) or one dot2 per pair (values: fp16 weights)
+// accumulates in fp32.  No MFMA: one query per head makes this a bandwidth-bound GEMV.
+//
+// Work split: grid.x = packed-token splits (+1 workgroup for the fp16 ring),
+// grid.y = (sequence, kv head), grid.z = layer (or layer pair).  A workgroup has 4 waves;
+// each wave walks tiles of 128 tokens.  In a tile, a 16-lane row owns one 32-token block:
+//   key phase    lane = 2 tokens x all channels; the weights q*s^ come from LDS
+//   value phase  lane = D/64 channels x all 128 tokens; the weights p*s^ come from LDS
+// Every "virtual head" v = (layer in pair) * NREP + (query head in GQA group) has its own
+// weights and accumulators and shares the unpacked codes.
+#include "xq_internal.h"
+
+#if !defined(XQ_D) || !defined(XQ_G) || !defined(XQ_BK) || !defined(XQ_BV)
+#error "compile with -DXQ_D= -DXQ_G= -DXQ_BK= -DXQ_BV= (one translation unit per configuration)"
+#endif
+
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float hbits(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
+
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {  // sum over aligned groups of W lanes
+#pragma unroll
+    for (int o = W / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+template <int N>
+struct VecLoad;
+template <>
+struct VecLoad<1> {
+    static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) { o[0] = *p; }
+};
+template <>
+struct VecLoad<2> {
+    static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) {
+        uint2 v = *(const uint2 *)p;
+        o[0] = v.x;
+        o[1] = v.y;
+    }
+};
+template <>
+struct VecLoad<4> {
+    static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) {
+        uint4 v = *(const uint4 *)p;
+        o[0] = v.x;
+        o[1] = v.y;
+        o[2] = v.z;
+        o[3] = v.w;
+    }
+};
+template <>
+struct VecLoad<8> {
+    static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) {
+        VecLoad<4>::ld(p, o);
+        VecLoad<4>::ld(p + 4, o + 4);
+    }
+};
+
+// Partial result of one split for one query head: unnormalised output, running max
+// (log2 domain) and denominator.
+struct Partial {
+    static constexpr int EXTRA = 2;
+};
+
+template <int D, int G, int BK, int BV, int NREP, int NLAY>
+__global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
+    constexpr int NV = NREP * NLAY;       // virtual heads
+    constexpr int CPL = D / 64;           // value channels per lane
+    constexpr int NJ = D / G;             // value groups per token
+    constexpr int NGT = XQ_TILE_TOKENS / G;  // key groups per tile
+    constexpr int LPG = 64 / NGT;         // lanes preparing one key group
+    constexpr int CPP = D / LPG;          // channels per lane in the key-weight prep
+    constexpr int WK = D * BK / 32;       // words per key row
+    constexpr int CWK = WK < 4 ? WK : 4;  // words per chunk
+    constexpr int NCH = WK / CWK;
+    constexpr int PERK = 32 / BK;         // key codes per word
+    constexpr int HALFK = PERK / 2;       // ... per 16-bit half
+    constexpr int BYTEK = 8 / BK;         // ... per byte
+    constexpr int WS = CPL * BV;          // value words per slot per block
+    constexpr int PERV = 32 / BV;
+    constexpr int TPW = PERV / CPL;       // tokens per value word
+    constexpr int HALFV = PERV / 2;       // value codes per half
+    constexpr uint32_t MASKK = ((1u << BK) - 1u) * 0x00010001u;
+    constexpr uint32_t MASKV = ((1u << BV) - 1u) * 0x00010001u;
+    static_assert(CPP >= 2 && CPP <= 8, "prep width");
+
+    // per wave: key weights q * s^ (pre-scaled) and value weights p * s^ (pre-scaled, pair order);
+    // the cross-wave combine at the end reuses the key-weight space
+    typedef float KwT[NV][NGT][D];
+    typedef _Float16 VwT[NV][4][NJ][32];
+    typedef float PartT[NV][D + 2];
+    constexpr int KW_BYTES = 4 * (int)sizeof(KwT), PART_BYTES = 4 * (int)sizeof(PartT);
+    __shared__ __attribute__((aligned(16))) char s_raw[(KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES) + 4 * sizeof(VwT)];
+    KwT *s_kw = (KwT *)s_raw;
+    VwT *s_vw = (VwT *)(s_raw + (KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES));
+    PartT *s_part = (PartT *)s_raw;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int split = blockIdx.x, bh = blockIdx.y;
+    const int layer = a.layer0 + blockIdx.z * NLAY;
+    const int bi = bh / a.n_kv_heads, hkv = bh % a.n_kv_heads;
+    const int row = lane >> 4, r16 = lane & 15;
+    const int n_blocks = a.Tq / 32;
+
+    XqLayerDesc dsc[NLAY];
+#pragma unroll
+    for (int y = 0; y < NLAY; ++y) dsc[y] = a.layers[layer + y];
+
+    auto qptr = [&](int v) -> const uint16_t * {  // query of virtual head v
+        int y = v / NREP, n = v % NREP;
+        return a.q + (((int64_t)(blockIdx.z * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) * D;
+    };
+
+    float m_run[NV], l_run[NV];
+    float accv[NV][CPL];
+    float zacc[NV][NJ];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        m_run[v] = -INFINITY;
+        l_run[v] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) accv[v][c] = 0.f;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) zacc[v][j] = 0.f;
+    }
+
+    if (split < a.n_splits) {
+        // ------------------------------------------------------------ packed tokens
+        const int gi = lane / LPG, li = lane % LPG;  // key-weight prep role
+        float qk[NV][CPP], qz[NV][CPP];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const uint16_t *qp = qptr(v);
+#pragma unroll
+            for (int k = 0; k < CPP; ++k) {
+                int c = li * CPP + k;
+                float qv = hbits(qp[c]) * a.scale_log2e;
+                qz[v][k] = qv;
+                // the code of channel c arrives as c * 2^((BK*c) mod 8 - 24)
+                qk[v][k] = qv * __builtin_ldexpf(1.0f, 24 - ((BK * c) & 7));
+            }
+        }
+        const int tile_end = min((split + 1) * a.tiles_per_split, (n_blocks + 3) / 4);
+        for (int tile = split * a.tiles_per_split + wave; tile < tile_end; tile += 4) {
+            const int blk = tile * 4 + row;
+            const bool row_ok = blk < n_blocks;
+            // ---- key weights for the tile's groups -> LDS
+            float zs[NV];
+            {
+                const int Gidx = tile * NGT + gi;
+                const bool g_ok = Gidx * G < a.Tq;
+                uint32_t meta[NLAY][CPP];
+#pragma unroll
+                for (int y = 0; y < NLAY; ++y) {
+                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + (int64_t)bh * a.st.k_meta) +
+                                         (int64_t)Gidx * D + li * CPP;
+                    if (g_ok) VecLoad<CPP>::ld(mp, meta[y]);
+                    else {
+#pragma unroll
+                        for (int k = 0; k < CPP; ++k) meta[y][k] = 0;
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    float zp = 0.f;
+#pragma unroll
+                    for (int k = 0; k < CPP; ++k) {
+                        uint32_t m = meta[v / NREP][k];
+                        s_kw[wave][v][gi][li * CPP + k] = qk[v][k] * hbits(m & 0xffffu);
+                        zp = fmaf(qz[v][k], hbits(m >> 16), zp);
+                    }
+                    zs[v] = group_sum<LPG>(zp);
+                }
+            }
+            // ---- this lane's two key rows (tokens r16 and r16 + 16 of block blk)
+            uint32_t kc[2][WK];
+            {
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
+                                                        (int64_t)bh * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
+                                     (int64_t)blk * 32 * WK;
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        if (row_ok) VecLoad<CWK>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
+                        else {
+#pragma unroll
+                            for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
+                        }
+                    }
+            }
+            // ---- value codes of the tile for this lane's channels, value metadata of its two tokens
+            uint32_t vc[4][WS];
+            {
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
+                                                        (int64_t)bh * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    const int b2 = tile * 4 + kb;
+                    if (b2 < n_blocks) VecLoad<WS>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[kb]);
+                    else {
+#pragma unroll
+                        for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
+                    }
+                }
+            }
+            uint32_t vm[NLAY][2][NJ];
+#pragma unroll
+            for (int y = 0; y < NLAY; ++y)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + (int64_t)bh * a.st.v_meta) +
+                                         ((int64_t)blk * 32 + r16 + 16 * s) * NJ;
+                    if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
+                    else {
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) vm[y][s][j] = 0;
+                    }
+                }
+            wave_lds_fence();
+            // ---- q . K^ over the packed codes
+            float sc[2][NV];
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int v = 0; v < NV; ++v) sc[s][v] = 0.f;
+            const int kg = (row * 32) / G;  // key group of this row inside the tile
+#pragma unroll
+            for (int wi = 0; wi < WK; ++wi) {
+#pragma unroll
+                for (int src = 0; src < 2; ++src) {
+#pragma unroll
+                    for (int p4 = 0; p4 < BYTEK; p4 += 4) {
+                        // channels [base, base+4) in the low halves, [base + HALFK, ..+4) in the high halves
+                        const int base = wi * PERK + src * BYTEK + p4;
+                        float wlo[NV][4], whi[NV][4];
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            float4 t0 = *(const float4 *)&s_kw[wave][v][kg][base];
+                            float4 t1 = *(const float4 *)&s_kw[wave][v][kg][base + HALFK];
+                            wlo[v][0] = t0.x; wlo[v][1] = t0.y; wlo[v][2] = t0.z; wlo[v][3] = t0.w;
+                            whi[v][0] = t1.x; whi[v][1] = t1.y; whi[v][2] = t1.z; whi[v][3] = t1.w;
+                        }
+#pragma unroll
+                        for (int s = 0; s < 2; ++s) {
+                            const uint32_t x = src ? (kc[s][wi] >> 8) : kc[s][wi];
+#pragma unroll
+                            for (int p = 0; p < 4; ++p) {
+                                half2_t c2 = __builtin_bit_cast(half2_t, x & (MASKK << (BK * (p4 + p))));
+#pragma unroll
+                                for (int v = 0; v < NV; ++v) {
+                                    sc[s][v] = fmaf(wlo[v][p], (float)c2.x, sc[s][v]);
+                                    sc[s][v] = fmaf(whi[v][p], (float)c2.y, sc[s][v]);
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+            // ---- online softmax bookkeeping (log2 domain), value weights -> LDS
+            // The value weights p * s^ travel as fp16.  A token whose largest value scale is
+            // >= 2^9 raises the softmax reference by the excess exponent, which keeps every
+            // weight below 2^15 for any fp16 input; for ordinary scales this adds nothing.
+            float eadd[NLAY][2];
+#pragma unroll
+            for (int y = 0; y < NLAY; ++y)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    uint32_t hmax = 0;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) hmax = max(hmax, vm[y][s][j] & 0x7fffu);
+                    eadd[y][s] = (float)max((int)(hmax >> 10) - 23, 0);
+                }
+            float pr[2][NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                float u0 = row_ok ? sc[0][v] + zs[v] : -INFINITY;
+                float u1 = row_ok ? sc[1][v] + zs[v] : -INFINITY;
+                float tmax = wave_max(fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]));
+                float m_new = fmaxf(m_run[v], tmax);
+                if (m_new > m_run[v]) {  // wave-uniform
+                    float alpha = exp2f(m_run[v] - m_new);  // m_run = -inf gives 0
+                    l_run[v] *= alpha;
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) accv[v][c] *= alpha;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) zacc[v][j] *= alpha;
+                    m_run[v] = m_new;
+                }
+                pr[0][v] = exp2f(u0 - m_new);
+                pr[1][v] = exp2f(u1 - m_new);
+                l_run[v] += pr[0][v] + pr[1][v];
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int tau = r16 + 16 * s;          // token inside the block
+                const int tw = tau % TPW;              // ... inside its value word
+                const int pos = (tau / TPW) * TPW + 2 * (tw % (TPW / 2)) + tw / (TPW / 2);  // pair order
+                const float tsc = __builtin_ldexpf(1.0f, 6 - ((BV * CPL * tw) & 7));
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        uint32_t m = vm[v / NREP][s][j];
+                        s_vw[wave][v][row][j][pos] = (_Float16)(pr[s][v] * hbits(m & 0xffffu) * tsc);
+                        zacc[v][j] = fmaf(pr[s][v], hbits(m >> 16), zacc[v][j]);
+                    }
+            }
+            wave_lds_fence();
+            // ---- P . V^ over the packed codes
+            const int jl = (lane * CPL) / G;  // channel group of this lane's channels
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                if (tile * 4 + kb >= n_blocks) break;  // wave-uniform
+#pragma unroll
+                for (int m = 0; m < WS; ++m) {
+#pragma unroll
+                    for (int i0 = 0; i0 < TPW / 2; i0 += 4) {
+                        half2_t w2[NV][4];
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            uint4 t = *(const uint4 *)&s_vw[wave][v][kb][jl][m * TPW + 2 * i0];
+                            w2[v][0] = __builtin_bit_cast(half2_t, t.x);
+                            w2[v][1] = __builtin_bit_cast(half2_t, t.y);
+                            w2[v][2] = __builtin_bit_cast(half2_t, t.z);
+                            w2[v][3] = __builtin_bit_cast(half2_t, t.w);
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+#pragma unroll
+                            for (int c = 0; c < CPL; ++c) {
+                                const int eh = (i0 + i) * CPL + c;      // code index inside a half
+                                const int bit = BV * eh;                 // < 16
+                                const uint32_t x = (bit >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                                half2_t c2 = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
+#pragma unroll
+                                for (int v = 0; v < NV; ++v)
+                                    accv[v][c] = __builtin_amdgcn_fdot2(w2[v][i], c2, accv[v][c], false);
+                            }
+                    }
+                }
+            }
+            wave_lds_fence();
+        }
+        // ---- wave totals
+        const int jl = (lane * CPL) / G;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            l_run[v] = group_sum<64>(l_run[v]);
+            float zj[NJ];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) zj[j] = group_sum<64>(zacc[v][j]);
+            float zsel = zj[0];
+#pragma unroll
+            for (int j = 1; j < NJ; ++j) zsel = (jl == j) ? zj[j] : zsel;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                accv[v][c] = accv[v][c] * __builtin_ldexpf(1.0f, 18 - BV * c) + zsel;
+        }
+    } else {
+        // ------------------------------------------------------------ fp16 ring (newest tokens)
+        float qf[NV][CPL];
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) qf[v][c] = hbits(qptr(v)[lane * CPL + c]) * a.scale_log2e;
+        const int r = a.T - a.Tq;
+        for (int i = wave; i < r; i += 4) {
+            const int slot = (a.Tq + i) % a.R;
+#pragma unroll
+            for (int y = 0; y < NLAY; ++y) {
+                const uint16_t *kp = (const uint16_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + slot * D + lane * CPL;
+                const uint16_t *vp = (const uint16_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + slot * D + lane * CPL;
+                float kf[CPL], vf[CPL];
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    kf[c] = hbits(kp[c]);
+                    vf[c] = hbits(vp[c]);
+                }
+#pragma unroll
+                for (int n = 0; n < NREP; ++n) {
+                    const int v = y * NREP + n;
+                    float part = 0.f;
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) part = fmaf(qf[v][c], kf[c], part);
+                    float u = group_sum<64>(part);
+                    float m_new = fmaxf(m_run[v], u);
+                    float alpha = exp2f(m_run[v] - m_new);
+                    float p = exp2f(u - m_new);
+                    l_run[v] = l_run[v] * alpha + p;
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) accv[v][c] = fmaf(p, vf[c], accv[v][c] * alpha);
+                    m_run[v] = m_new;
+                }
+            }
+        }
+    }
+
+    // ---------------------------------------------------------------- combine the 4 waves
+    __syncthreads();  // every wave is done with the key weights before their space is reused
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) s_part[wave][v][lane * CPL + c] = accv[v][c];
+        if (lane == 0) {
+            s_part[wave][v][D] = m_run[v];
+            s_part[wave][v][D + 1] = l_run[v];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < NV * (D + 2); idx += 256) {
+        const int v = idx / (D + 2), e = idx % (D + 2);
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, s_part[w][v][D]);
+        float val;
+        if (e == D) {
+            val = M;
+        } else {
+            val = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float mw = s_part[w][v][D];
+                float f = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
+                val += f * s_part[w][v][e];
+            }
+        }
+        const int y = v / NREP, n = v % NREP;
+        float *wp = a.ws + ((((int64_t)(blockIdx.z * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) *
+                                (a.n_splits + 1) + split) * (D + 2);
+        wp[e] = val;
+    }
+}
+
+template <int NREP>
+hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipStream_t s) {
+    constexpr int D = XQ_D, G = XQ_G, BK = XQ_BK, BV = XQ_BV;
+    dim3 block(256);
+    if (pair_fused) {
+        // 2 * NREP virtual heads must fit the LDS weight tables
+        if constexpr (2 * NREP * (XQ_TILE_TOKENS / G) <= 16 && (D == 128 || NREP == 1)) {
+            dim3 grid(a.n_splits + 1, a.batch * a.n_kv_heads, n_layers / 2);
+            xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(a);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else {
+        dim3 grid(a.n_splits + 1, a.batch * a.n_kv_heads, n_layers);
+        xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+#define XQ_CAT2(a, b, c, d) xq_launch_decode_##a##_##b##_##c##d
+#define XQ_CAT(a, b, c, d) XQ_CAT2(a, b, c, d)
+
+// One translation unit per (head_dim, group, key bits, value bits); n_rep = query heads per kv head.
+hipError_t XQ_CAT(XQ_D, XQ_G, XQ_BK, XQ_BV)(const XqDecodeArgs &a, int n_rep, int n_layers, int pair_fused,
+                                            hipStream_t s) {
+    switch (n_rep) {
+        case 1: return launch_cfg<1>(a, n_layers, pair_fused, s);
+#if XQ_D == 128
+        case 2: return launch_cfg<2>(a, n_layers, pair_fused, s);
+        case 4: return launch_cfg<4>(a, n_layers, pair_fused, s);
+#endif
+        default: return hipErrorInvalidValue;
+    }
+}

@@ -1,0 +1,450 @@
+// Host layer of libxq: configuration checks, arena carving, length bookkeeping and
+// the dispatch of the C-ABI entry points declared in include/xq.h onto the kernels.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "xq_internal.h"
+
+namespace {
+
+inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
+
+inline int bits_of(const xq_config &c, int l, bool is_v) { return l < (is_v ? c.vq : c.kq) ? 2 : 1; }
+// Appendix Alg. 1 (with the dequantization loop's conditions): a layer stores codes
+// iff it is below the sharing start or is the even layer of its pair.
+inline bool stores_codes(const xq_config &c, int l, bool is_v) { return l < (is_v ? c.vm : c.km) || (l % 2 == 0); }
+
+int check_config(const xq_config *c) {
+    if (!c) return XQ_ERR_INVALID_ARG;
+    if (c->n_layers < 1 || c->n_layers > XQ_MAX_LAYERS || c->batch < 1 || c->n_kv_heads < 1 ||
+        c->n_q_heads < 1 || c->max_tokens < 1)
+        return XQ_ERR_INVALID_ARG;
+    if (c->n_q_heads % c->n_kv_heads) return XQ_ERR_INVALID_ARG;
+    if (c->kq < 0 || c->vq < 0 || c->km < 0 || c->vm < 0) return XQ_ERR_INVALID_ARG;
+    if (!(c->eta1 >= 0.0f && c->eta1 < 0.5f) || !(c->eta2 >= 0.0f && c->eta2 < 0.5f)) return XQ_ERR_INVALID_ARG;
+    if (c->head_dim != 64 && c->head_dim != 128) return XQ_ERR_UNSUPPORTED;
+    if (c->group != 32 && c->group != 64) return XQ_ERR_UNSUPPORTED;
+    if (c->group > c->head_dim) return XQ_ERR_UNSUPPORTED;
+    if (c->residual < c->group || c->residual % c->group || c->residual > 1024) return XQ_ERR_INVALID_ARG;
+    int rep = c->n_q_heads / c->n_kv_heads;
+    if (rep != 1 && rep != 2 && rep != 4) return XQ_ERR_UNSUPPORTED;
+    if (c->head_dim == 64 && rep != 1) return XQ_ERR_UNSUPPORTED;
+    // the two layers of a sharing pair must have one bit width
+    for (int l = 1; l < c->n_layers; l += 2) {
+        if (!stores_codes(*c, l, false) && bits_of(*c, l, false) != bits_of(*c, l - 1, false)) return XQ_ERR_INVALID_ARG;
+        if (!stores_codes(*c, l, true) && bits_of(*c, l, true) != bits_of(*c, l - 1, true)) return XQ_ERR_INVALID_ARG;
+    }
+    return XQ_OK;
+}
+
+struct Carve {
+    XqStrides st;
+    int64_t total;
+};
+
+// Lays the regions out; fills descs when not null.
+Carve carve(const xq_config &c, XqLayerDesc *descs) {
+    Carve r;
+    const int64_t D = c.head_dim, g = c.group, R = c.residual;
+    const int64_t maxTq = xq_quantized_len(c.max_tokens, c.group, c.residual);
+    const int64_t nbh = (int64_t)c.batch * c.n_kv_heads;
+    r.st.k_codes2 = maxTq * D * 2 / 8;
+    r.st.k_codes1 = maxTq * D * 1 / 8;
+    r.st.v_codes2 = r.st.k_codes2;
+    r.st.v_codes1 = r.st.k_codes1;
+    r.st.k_meta = (maxTq / g) * D * 4;
+    r.st.v_meta = maxTq * (D / g) * 4;
+    r.st.res = R * D * 2;
+    int64_t off = align256((int64_t)sizeof(XqLayerDesc) * c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        XqLayerDesc d;
+        d.bk = bits_of(c, l, false);
+        d.bv = bits_of(c, l, true);
+        d.k_store = stores_codes(c, l, false);
+        d.v_store = stores_codes(c, l, true);
+        if (d.k_store) {
+            d.k_codes = off;
+            off = align256(off + nbh * (d.bk == 2 ? r.st.k_codes2 : r.st.k_codes1));
+        } else {
+            d.k_codes = descs ? descs[l - 1].k_codes : 0;
+        }
+        if (d.v_store) {
+            d.v_codes = off;
+            off = align256(off + nbh * (d.bv == 2 ? r.st.v_codes2 : r.st.v_codes1));
+        } else {
+            d.v_codes = descs ? descs[l - 1].v_codes : 0;
+        }
+        d.k_meta = off;
+        off = align256(off + nbh * r.st.k_meta);
+        d.v_meta = off;
+        off = align256(off + nbh * r.st.v_meta);
+        d.k_res = off;
+        off = align256(off + nbh * r.st.res);
+        d.v_res = off;
+        off = align256(off + nbh * r.st.res);
+        if (descs) descs[l] = d;
+    }
+    r.total = off;
+    return r;
+}
+
+int max_splits_for(int Tq) {
+    int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
+    return tiles > XQ_MAX_SPLITS ? XQ_MAX_SPLITS : tiles;
+}
+
+size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
+    return (size_t)n_layers * c.batch * c.n_q_heads * (size_t)(n_splits + 1) * (c.head_dim + 2);
+}
+
+// Split plan: whole tiles of 128 tokens per split, at least one tile per wave of a
+// workgroup, enough workgroups to fill 256 CUs several times over, at most XQ_MAX_SPLITS.
+void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int *tiles_per_split) {
+    const xq_config &c = cache->cfg;
+    int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
+    if (tiles == 0) {
+        *n_splits = 0;
+        *tiles_per_split = 4;
+        return;
+    }
+    int64_t units = (int64_t)tiles * c.batch * c.n_kv_heads * n_layers;
+    int tps = (int)((units + 8191) / 8192);
+    if (tps < 4) tps = 4;
+    if (tps > 32) tps = 32;
+    if (cache->tiles_per_split_override > 0) tps = cache->tiles_per_split_override;
+    int min_tps = (tiles + XQ_MAX_SPLITS - 1) / XQ_MAX_SPLITS;
+    if (tps < min_tps) tps = min_tps;
+    *tiles_per_split = tps;
+    *n_splits = (tiles + tps - 1) / tps;
+}
+
+bool range_ok(const xq_cache *c, int layer0, int n) {
+    return c && layer0 >= 0 && n >= 1 && layer0 + n <= c->cfg.n_layers;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *xq_strerror(int code) {
+    switch (code) {
+        case XQ_OK: return "ok";
+        case XQ_ERR_INVALID_ARG: return "invalid argument";
+        case XQ_ERR_UNSUPPORTED: return "unsupported head_dim / group / head ratio";
+        case XQ_ERR_CAPACITY: return "capacity exceeded (max_tokens, arena or workspace)";
+        case XQ_ERR_STATE: return "call not valid in the cache's current state";
+        case XQ_ERR_HIP: return "HIP call or kernel launch failed";
+        default: return "unknown error code";
+    }
+}
+
+int xq_cache_bytes(const xq_config *cfg, size_t *arena_bytes, size_t *workspace_bytes) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    Carve cv = carve(*cfg, nullptr);
+    if (arena_bytes) *arena_bytes = (size_t)cv.total;
+    if (workspace_bytes) {
+        int maxTq = xq_quantized_len(cfg->max_tokens, cfg->group, cfg->residual);
+        *workspace_bytes = workspace_floats(*cfg, cfg->n_layers, max_splits_for(maxTq)) * sizeof(float);
+    }
+    return XQ_OK;
+}
+
+int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, xq_cache **out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!dev_arena || !out || ((uintptr_t)dev_arena & 255)) return XQ_ERR_INVALID_ARG;
+    xq_cache *c = new (std::nothrow) xq_cache;
+    if (!c) return XQ_ERR_INVALID_ARG;
+    memset(c, 0, sizeof(*c));
+    c->cfg = *cfg;
+    Carve cv = carve(*cfg, c->layers);
+    if ((size_t)cv.total > arena_bytes) {
+        delete c;
+        return XQ_ERR_CAPACITY;
+    }
+    c->strides = cv.st;
+    c->arena = (char *)dev_arena;
+    c->arena_bytes = arena_bytes;
+    c->dev_layers = (XqLayerDesc *)dev_arena;
+    if (hipMemcpy(c->dev_layers, c->layers, sizeof(XqLayerDesc) * cfg->n_layers, hipMemcpyHostToDevice) != hipSuccess) {
+        delete c;
+        return XQ_ERR_HIP;
+    }
+    *out = c;
+    return XQ_OK;
+}
+
+void xq_cache_destroy(xq_cache *cache) { delete cache; }
+
+int xq_cache_reset(xq_cache *cache) {
+    if (!cache) return XQ_ERR_INVALID_ARG;
+    memset(cache->len, 0, sizeof(cache->len));
+    return XQ_OK;
+}
+
+int xq_cache_len(const xq_cache *cache, int32_t layer, int32_t *T, int32_t *T_q) {
+    if (!range_ok(cache, layer, 1)) return XQ_ERR_INVALID_ARG;
+    if (T) *T = cache->len[layer];
+    if (T_q) *T_q = xq_quantized_len(cache->len[layer], cache->cfg.group, cache->cfg.residual);
+    return XQ_OK;
+}
+
+int xq_cache_layout(const xq_cache *cache, int32_t layer, int64_t offsets[6], int64_t sizes[6]) {
+    if (!range_ok(cache, layer, 1) || !offsets || !sizes) return XQ_ERR_INVALID_ARG;
+    const XqLayerDesc &d = cache->layers[layer];
+    const XqStrides &s = cache->strides;
+    offsets[0] = d.k_store ? d.k_codes : -1;
+    offsets[1] = d.v_store ? d.v_codes : -1;
+    offsets[2] = d.k_meta;
+    offsets[3] = d.v_meta;
+    offsets[4] = d.k_res;
+    offsets[5] = d.v_res;
+    sizes[0] = d.bk == 2 ? s.k_codes2 : s.k_codes1;
+    sizes[1] = d.bv == 2 ? s.v_codes2 : s.v_codes1;
+    sizes[2] = s.k_meta;
+    sizes[3] = s.v_meta;
+    sizes[4] = s.res;
+    sizes[5] = s.res;
+    return XQ_OK;
+}
+
+void xq_debug_set_tiles_per_split(xq_cache *cache, int32_t tiles_per_split) {
+    if (cache) cache->tiles_per_split_override = tiles_per_split;
+}
+
+static void fill_pack_consts(const xq_config &c, XqPackArgs &a) {
+    // eta_B * (2^B - 1) and 1 - 2 eta_B, each one fp32 operation (Eq. 12)
+    volatile float e1 = c.eta1, e2 = c.eta2;
+    volatile float t1 = 2.0f * e1, t2 = 2.0f * e2;
+    a.c1_1 = e1 * 1.0f;
+    a.c2_1 = 1.0f - t1;
+    a.c1_2 = e2 * 3.0f;
+    a.c2_2 = 1.0f - t2;
+}
+
+int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
+                     const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream) {
+    if (!range_ok(cache, layer0, n_layers) || !k_f16 || !v_f16 || !strides || T < 1) return XQ_ERR_INVALID_ARG;
+    const xq_config &c = cache->cfg;
+    if (T > c.max_tokens) return XQ_ERR_CAPACITY;
+    for (int i = 0; i < 4; ++i)
+        if (strides[i] < 0 || strides[i] % 8) return XQ_ERR_INVALID_ARG;
+    if (strides[3] < c.head_dim || ((uintptr_t)k_f16 & 15) || ((uintptr_t)v_f16 & 15)) return XQ_ERR_INVALID_ARG;
+    for (int l = layer0; l < layer0 + n_layers; ++l)
+        if (cache->len[l] != 0) return XQ_ERR_STATE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int Tq = xq_quantized_len(T, c.group, c.residual);
+    if (Tq > 0) {
+        XqPackArgs a;
+        memset(&a, 0, sizeof(a));
+        a.arena = cache->arena;
+        a.layers = cache->dev_layers;
+        a.st = cache->strides;
+        a.layer0 = layer0;
+        a.batch = c.batch;
+        a.n_kv_heads = c.n_kv_heads;
+        a.R = c.residual;
+        a.k_src = (const uint16_t *)k_f16;
+        a.v_src = (const uint16_t *)v_f16;
+        a.s_layer = strides[0];
+        a.s_batch = strides[1];
+        a.s_head = strides[2];
+        a.s_tok = strides[3];
+        a.from_ring = 0;
+        a.src_tok0 = 0;
+        a.dst_tok0 = 0;
+        a.n_groups = Tq / c.group;
+        fill_pack_consts(c, a);
+        if (xq_launch_pack(a, c.head_dim, c.group, n_layers, s) != hipSuccess) return XQ_ERR_HIP;
+    }
+    XqRingArgs r;
+    memset(&r, 0, sizeof(r));
+    r.arena = cache->arena;
+    r.layers = cache->dev_layers;
+    r.st = cache->strides;
+    r.layer0 = layer0;
+    r.batch = c.batch;
+    r.n_kv_heads = c.n_kv_heads;
+    r.R = c.residual;
+    r.D = c.head_dim;
+    r.k_src = (const uint16_t *)k_f16;
+    r.v_src = (const uint16_t *)v_f16;
+    r.s_layer = strides[0];
+    r.s_batch = strides[1];
+    r.s_head = strides[2];
+    r.s_tok = strides[3];
+    r.src_tok0 = Tq;
+    r.dst_tok0 = Tq;
+    r.n_tok = T - Tq;
+    if (xq_launch_ring_write(r, n_layers, s) != hipSuccess) return XQ_ERR_HIP;
+    for (int l = layer0; l < layer0 + n_layers; ++l) cache->len[l] = T;
+    return XQ_OK;
+}
+
+int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_new_f16,
+                    const void *v_new_f16, void *hip_stream) {
+    if (!range_ok(cache, layer0, n_layers) || !k_new_f16 || !v_new_f16) return XQ_ERR_INVALID_ARG;
+    if (((uintptr_t)k_new_f16 & 15) || ((uintptr_t)v_new_f16 & 15)) return XQ_ERR_INVALID_ARG;
+    const xq_config &c = cache->cfg;
+    for (int l = layer0; l < layer0 + n_layers; ++l)
+        if (cache->len[l] >= c.max_tokens) return XQ_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t D = c.head_dim;
+    const int64_t per_layer = (int64_t)c.batch * c.n_kv_heads * D;
+    // runs of consecutive layers with one length share their launches
+    int l = layer0;
+    while (l < layer0 + n_layers) {
+        int e = l + 1;
+        while (e < layer0 + n_layers && cache->len[e] == cache->len[l]) ++e;
+        const int T = cache->len[l];
+        const int Tq = xq_quantized_len(T, c.group, c.residual);
+        if (T - Tq == c.residual) {  // ring full: its oldest g tokens become a packed group
+            XqPackArgs a;
+            memset(&a, 0, sizeof(a));
+            a.arena = cache->arena;
+            a.layers = cache->dev_layers;
+            a.st = cache->strides;
+            a.layer0 = l;
+            a.batch = c.batch;
+            a.n_kv_heads = c.n_kv_heads;
+            a.R = c.residual;
+            a.from_ring = 1;
+            a.src_tok0 = Tq % c.residual;
+            a.dst_tok0 = Tq;
+            a.n_groups = 1;
+            fill_pack_consts(c, a);
+            if (xq_launch_pack(a, c.head_dim, c.group, e - l, s) != hipSuccess) return XQ_ERR_HIP;
+        }
+        XqRingArgs r;
+        memset(&r, 0, sizeof(r));
+        r.arena = cache->arena;
+        r.layers = cache->dev_layers;
+        r.st = cache->strides;
+        r.layer0 = l;
+        r.batch = c.batch;
+        r.n_kv_heads = c.n_kv_heads;
+        r.R = c.residual;
+        r.D = c.head_dim;
+        r.k_src = (const uint16_t *)k_new_f16 + (int64_t)(l - layer0) * per_layer;
+        r.v_src = (const uint16_t *)v_new_f16 + (int64_t)(l - layer0) * per_layer;
+        r.s_layer = per_layer;
+        r.s_batch = (int64_t)c.n_kv_heads * D;
+        r.s_head = D;
+        r.s_tok = D;
+        r.src_tok0 = 0;
+        r.dst_tok0 = T;
+        r.n_tok = 1;
+        if (xq_launch_ring_write(r, e - l, s) != hipSuccess) return XQ_ERR_HIP;
+        for (int k = l; k < e; ++k) cache->len[k] = T + 1;
+        l = e;
+    }
+    return XQ_OK;
+}
+
+int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
+                        void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
+                        int32_t flags, void *hip_stream) {
+    if (!range_ok(cache, layer0, n_layers) || !q_f16 || !out_f32 || !dev_workspace) return XQ_ERR_INVALID_ARG;
+    if (flags & ~XQ_DECODE_PAIR_FUSED) return XQ_ERR_INVALID_ARG;
+    if (((uintptr_t)q_f16 & 3) || ((uintptr_t)out_f32 & 3) || ((uintptr_t)dev_workspace & 15)) return XQ_ERR_INVALID_ARG;
+    const xq_config &c = cache->cfg;
+    const int T = cache->len[layer0];
+    if (T < 1) return XQ_ERR_STATE;
+    for (int l = layer0; l < layer0 + n_layers; ++l)
+        if (cache->len[l] != T) return XQ_ERR_STATE;
+    const int Tq = xq_quantized_len(T, c.group, c.residual);
+    int n_splits, tps;
+    plan_splits(cache, Tq, n_layers, &n_splits, &tps);
+    if (workspace_floats(c, n_layers, n_splits) * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t per_layer_q = (int64_t)c.batch * c.n_q_heads * c.head_dim;
+    const int64_t per_layer_ws = (int64_t)c.batch * c.n_q_heads * (n_splits + 1) * (c.head_dim + 2);
+    const int rep = c.n_q_heads / c.n_kv_heads;
+    // runs of layers with one (bk, bv) and one fusion mode share a launch
+    int l = layer0;
+    while (l < layer0 + n_layers) {
+        const XqLayerDesc &d0 = cache->layers[l];
+        auto fusable = [&](int a) {  // pair (a, a+1) inside the range sharing keys and values
+            return (flags & XQ_DECODE_PAIR_FUSED) && xq_decode_can_fuse(c.head_dim, c.group, rep) && a % 2 == 0 && a + 1 < layer0 + n_layers &&
+                   !cache->layers[a + 1].k_store && !cache->layers[a + 1].v_store;
+        };
+        const bool fused = fusable(l);
+        int e = l;
+        while (e < layer0 + n_layers) {
+            const XqLayerDesc &d = cache->layers[e];
+            if (d.bk != d0.bk || d.bv != d0.bv) break;
+            if (fused) {
+                if (!fusable(e)) break;
+                e += 2;
+            } else {
+                if (fusable(e)) break;
+                e += 1;
+            }
+        }
+        XqDecodeArgs a;
+        memset(&a, 0, sizeof(a));
+        a.arena = cache->arena;
+        a.layers = cache->dev_layers;
+        a.st = cache->strides;
+        a.layer0 = l;
+        a.batch = c.batch;
+        a.n_q_heads = c.n_q_heads;
+        a.n_kv_heads = c.n_kv_heads;
+        a.R = c.residual;
+        a.T = T;
+        a.Tq = Tq;
+        a.n_splits = n_splits;
+        a.tiles_per_split = tps;
+        a.q = (const uint16_t *)q_f16 + (int64_t)(l - layer0) * per_layer_q;
+        a.out = (float *)out_f32 + (int64_t)(l - layer0) * per_layer_q;
+        a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
+        a.scale_log2e = sm_scale * 1.4426950408889634f;
+        if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, rep, e - l, fused ? 1 : 0, s) != hipSuccess)
+            return XQ_ERR_HIP;
+        l = e;
+    }
+    return XQ_OK;
+}
+
+int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t *dev_codes_u8, void *hip_stream) {
+    if (!range_ok(cache, layer, 1) || !dev_codes_u8) return XQ_ERR_INVALID_ARG;
+    const xq_config &c = cache->cfg;
+    const XqLayerDesc &d = cache->layers[layer];
+    if (!(is_v ? d.v_store : d.k_store)) return XQ_ERR_STATE;
+    const int Tq = xq_quantized_len(cache->len[layer], c.group, c.residual);
+    if (Tq == 0) return XQ_ERR_STATE;
+    XqUnpackArgs a;
+    a.B = is_v ? d.bv : d.bk;
+    a.codes = cache->arena + (is_v ? d.v_codes : d.k_codes);
+    a.stride = is_v ? (a.B == 2 ? cache->strides.v_codes2 : cache->strides.v_codes1)
+                    : (a.B == 2 ? cache->strides.k_codes2 : cache->strides.k_codes1);
+    a.n_bh = c.batch * c.n_kv_heads;
+    a.Tq = Tq;
+    a.D = c.head_dim;
+    a.is_v = is_v ? 1 : 0;
+    a.out = dev_codes_u8;
+    return xq_launch_unpack(a, (hipStream_t)hip_stream) == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+double xq_equivalent_bits(const xq_config *cfg, int32_t include_metadata, int32_t T) {
+    if (check_config(cfg)) return -1.0;
+    const xq_config &c = *cfg;
+    double code_bits = 0.0;  // per element position, summed over layers and K/V
+    for (int l = 0; l < c.n_layers; ++l) {
+        if (stores_codes(c, l, false)) code_bits += bits_of(c, l, false);
+        if (stores_codes(c, l, true)) code_bits += bits_of(c, l, true);
+    }
+    if (!include_metadata) return code_bits / (2.0 * c.n_layers);
+    if (T < 1) return -1.0;
+    const double Tq = xq_quantized_len(T, c.group, c.residual), r = T - Tq;
+    // per channel of one (sequence, kv head): packed tokens carry codes + 32 bits of fp16
+    // scale/zero per group of g elements in every layer; ring tokens are 16-bit
+    double bits = Tq * code_bits + Tq * (32.0 / c.group) * 2.0 * c.n_layers + r * 16.0 * 2.0 * c.n_layers;
+    return bits / (2.0 * c.n_layers * T);
+}
+
+}  // extern "C"

@@ -1,0 +1,104 @@
+// Internal declarations shared by the host layer and the kernels of libxq.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xq.h"
+
+#define XQ_MAX_LAYERS 256
+#define XQ_MAX_SPLITS 64     // packed-token splits per (layer, sequence, kv head)
+#define XQ_TILE_TOKENS 128   // tokens one wave handles per iteration of the decode loop
+
+// Where a layer's regions live inside the arena (byte offsets) and what it holds.
+// k_codes / v_codes point at the codes the layer READS: its own, or those of the
+// layer below when it shares (Sec. 3.3.4: the dominant layer is the first of the pair).
+struct XqLayerDesc {
+    int64_t k_codes, v_codes;
+    int64_t k_meta, v_meta;
+    int64_t k_res, v_res;
+    int32_t bk, bv;            // bit width of keys / values
+    int32_t k_store, v_store;  // 1 if this layer writes codes
+};
+
+// Per (batch, kv head) strides in bytes; identical for every layer.
+struct XqStrides {
+    int64_t k_codes2, k_codes1;  // key codes at 2 / 1 bit
+    int64_t v_codes2, v_codes1;
+    int64_t k_meta, v_meta, res;
+};
+
+struct xq_cache {
+    xq_config cfg;
+    char *arena;
+    size_t arena_bytes;
+    XqLayerDesc layers[XQ_MAX_LAYERS];
+    XqLayerDesc *dev_layers;  // copy at the start of the arena
+    XqStrides strides;
+    int32_t len[XQ_MAX_LAYERS];
+    int32_t tiles_per_split_override;  // 0 = automatic
+};
+
+static inline int xq_quantized_len(int T, int g, int R) {
+    int over = T - R;
+    return over <= 0 ? 0 : g * ((over + g - 1) / g);
+}
+
+// ---- kernel launchers (defined in the .hip files); all return a hipError_t ----
+struct XqPackArgs {
+    char *arena;
+    const XqLayerDesc *layers;  // device
+    XqStrides st;
+    int32_t layer0;
+    int32_t batch, n_kv_heads;
+    int32_t R;
+    // source: external tensor (from_ring = 0) or the layer's own fp16 ring (from_ring = 1)
+    const uint16_t *k_src, *v_src;
+    int64_t s_layer, s_batch, s_head, s_tok;  // element strides of the external tensor
+    int32_t from_ring;
+    int32_t src_tok0;   // first source token (external) or first ring slot (ring)
+    int32_t dst_tok0;   // first destination token (multiple of g)
+    int32_t n_groups;   // token groups of g to quantize
+    float c1_1, c2_1;   // eta1 * 1, 1 - 2 eta1     (1-bit)
+    float c1_2, c2_2;   // eta2 * 3, 1 - 2 eta2     (2-bit)
+};
+hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s);
+
+struct XqRingArgs {
+    char *arena;
+    const XqLayerDesc *layers;
+    XqStrides st;
+    int32_t layer0, batch, n_kv_heads, R, D;
+    const uint16_t *k_src, *v_src;
+    int64_t s_layer, s_batch, s_head, s_tok;
+    int32_t src_tok0;  // first source token
+    int32_t dst_tok0;  // absolute index of the first token written (slot = index mod R)
+    int32_t n_tok;
+};
+hipError_t xq_launch_ring_write(const XqRingArgs &a, int n_layers, hipStream_t s);
+
+struct XqDecodeArgs {
+    const char *arena;
+    const XqLayerDesc *layers;
+    XqStrides st;
+    int32_t layer0;
+    int32_t batch, n_q_heads, n_kv_heads;
+    int32_t R, T, Tq;
+    int32_t n_splits, tiles_per_split;
+    const uint16_t *q;  // [n_layers][b][h_q][D]
+    float *out;         // [n_layers][b][h_q][D]
+    float *ws;          // partials: [n_layers][b][h_q][n_splits + 1][D + 2]
+    float scale_log2e;  // sm_scale * log2(e)
+};
+// bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs
+hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv, int n_rep,
+                            int n_layers, int pair_fused, hipStream_t s);
+
+bool xq_decode_can_fuse(int D, int g, int n_rep);
+
+struct XqUnpackArgs {
+    const char *codes;  // region of the layer that stores them
+    int64_t stride;     // per (batch, kv head), bytes
+    int32_t n_bh, Tq, D, B, is_v;
+    uint8_t *out;
+};
+hipError_t xq_launch_unpack(const XqUnpackArgs &a, hipStream_t s);

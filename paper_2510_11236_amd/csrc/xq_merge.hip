@@ -1,0 +1,56 @@
+// Merge of the split-K partials and the dispatch onto the per-configuration decode kernels.
+#include "xq_internal.h"
+
+namespace {
+
+// Log-sum-exp merge: partial i holds the unnormalised output o_i[D], its running max m_i
+// (log2 domain) and denominator l_i.  out = sum_i o_i 2^(m_i - M) / sum_i l_i 2^(m_i - M).
+// One thread per output channel; the order over i is fixed, so the result does not depend
+// on which workgroup finished first.
+template <int D>
+__global__ __launch_bounds__(D) void xq_merge_kernel(const float *ws, float *out, int n_parts) {
+    const int64_t head = blockIdx.x;
+    const float *p = ws + head * n_parts * (D + 2);
+    float M = -INFINITY;
+    for (int i = 0; i < n_parts; ++i) M = fmaxf(M, p[i * (D + 2) + D]);
+    float num = 0.f, den = 0.f;
+    for (int i = 0; i < n_parts; ++i) {
+        float mi = p[i * (D + 2) + D];
+        float f = (mi == -INFINITY) ? 0.f : exp2f(mi - M);
+        num = fmaf(f, p[i * (D + 2) + threadIdx.x], num);
+        den = fmaf(f, p[i * (D + 2) + D + 1], den);
+    }
+    out[head * D + threadIdx.x] = num / den;
+}
+
+}  // namespace
+
+#define XQ_DECL(D, G, K, V) \
+    hipError_t xq_launch_decode_##D##_##G##_##K##V(const XqDecodeArgs &, int, int, int, hipStream_t);
+#define XQ_DECL_BITS(D, G) XQ_DECL(D, G, 1, 1) XQ_DECL(D, G, 1, 2) XQ_DECL(D, G, 2, 1) XQ_DECL(D, G, 2, 2)
+XQ_DECL_BITS(128, 32)
+XQ_DECL_BITS(128, 64)
+XQ_DECL_BITS(64, 32)
+XQ_DECL_BITS(64, 64)
+
+hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv, int n_rep, int n_layers,
+                            int pair_fused, hipStream_t s) {
+    hipError_t e = hipErrorInvalidValue;
+#define XQ_CASE(DD, GG, K, V) \
+    if (D == DD && g == GG && bk == K && bv == V) e = xq_launch_decode_##DD##_##GG##_##K##V(a, n_rep, n_layers, pair_fused, s);
+#define XQ_CASE_BITS(DD, GG) XQ_CASE(DD, GG, 1, 1) XQ_CASE(DD, GG, 1, 2) XQ_CASE(DD, GG, 2, 1) XQ_CASE(DD, GG, 2, 2)
+    XQ_CASE_BITS(128, 32)
+    XQ_CASE_BITS(128, 64)
+    XQ_CASE_BITS(64, 32)
+    XQ_CASE_BITS(64, 64)
+    if (e != hipSuccess) return e;
+    const int64_t heads = (int64_t)n_layers * a.batch * a.n_q_heads;
+    if (D == 128) xq_merge_kernel<128><<<dim3((unsigned)heads), dim3(128), 0, s>>>(a.ws, a.out, a.n_splits + 1);
+    else xq_merge_kernel<64><<<dim3((unsigned)heads), dim3(64), 0, s>>>(a.ws, a.out, a.n_splits + 1);
+    return hipGetLastError();
+}
+
+// Whether xq_launch_decode can serve a sharing pair with one workgroup for this shape.
+bool xq_decode_can_fuse(int D, int g, int n_rep) {
+    return 2 * n_rep * (XQ_TILE_TOKENS / g) <= 16 && (D == 128 || n_rep == 1);
+}

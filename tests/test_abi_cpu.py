@@ -1,0 +1,87 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and its
+host logic (config checks, sizes, accounting) behaves -- no GPU needed."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _gold(name):
+    rows = []
+    for line in open(os.path.join(ROOT, "tests", "golden", name)):
+        line = line.split("#")[0].strip()
+        if line:
+            rows.append(line.split())
+    return rows
+
+
+@pytest.fixture(scope="module")
+def xq():
+    import paper_2510_11236_amd as xq
+    xq.lib()
+    return xq
+
+
+def test_exports_every_declared_symbol(xq):
+    hdr = open(os.path.join(ROOT, "include", "xq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(xq_[a-z_0-9]+)\s*\(", hdr))
+    assert {"xq_quantize_pack", "xq_append_token", "xq_decode_attention"} <= names
+    L = xq.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+def _cfg(xq, **kw):
+    base = dict(n_layers=32, batch=4, n_q_heads=32, n_kv_heads=32, head_dim=128, group=32, residual=128,
+                max_tokens=32768 + 1, kq=32, vq=32, km=0, vm=0, eta1=1 / 6, eta2=0.045)
+    base.update(kw)
+    return xq.XqConfig(**base)
+
+
+def test_config_validation(xq):
+    assert xq.cache_bytes(_cfg(xq))[0] > 0
+    for bad, code in [(dict(head_dim=96), -2), (dict(group=16), -2), (dict(residual=100), -1), (dict(eta1=0.5), -1),
+                      (dict(eta2=-0.1), -1), (dict(n_q_heads=48), -1), (dict(n_q_heads=32, n_kv_heads=2), -2),
+                      (dict(n_layers=0), -1), (dict(kq=31, km=0), -1), (dict(vq=1, vm=0), -1),
+                      (dict(head_dim=64, n_q_heads=32, n_kv_heads=8), -2)]:
+        with pytest.raises(xq.XqError) as e:
+            xq.cache_bytes(_cfg(xq, **bad))
+        assert e.value.code == code, bad
+    # an odd boundary below the sharing start is fine: those layers do not share
+    assert xq.cache_bytes(_cfg(xq, kq=31, km=32))[0] > 0
+    assert xq.strerror(0) == "ok" and "capacity" in xq.strerror(-3)
+
+
+def test_arena_size_matches_bit_accounting(xq):
+    """cfg index 2: codes 1 bit/element (2-bit shared by pairs), metadata 1 bit/element at g=32."""
+    cfg = _cfg(xq)
+    arena, ws = xq.cache_bytes(cfg)
+    Tq, R, D, nbh, L = 32768 - 128 + 32, 128, 128, 4 * 32, 32   # max_tokens 32769 -> one more group
+    codes = 2 * (L // 2) * nbh * Tq * D * 2 // 8
+    meta = 2 * L * nbh * Tq * D * 4 // 32
+    res = 2 * L * nbh * R * D * 2
+    assert codes + meta + res <= arena <= codes + meta + res + 8 * L * 256 + 65536
+    assert ws > 0
+
+
+def test_equivalent_bits_golden(xq):
+    for L, kq, vq, km, vm, expect, *_ in _gold("equivalent_bits.txt"):
+        cfg = _cfg(xq, n_layers=int(L), kq=int(kq), vq=int(vq), km=int(km), vm=int(vm))
+        assert xq.equivalent_bits(cfg) == float(expect)
+
+
+def test_true_bits_include_metadata(xq):
+    # 2-bit, g = 32, all pairs shared, T = 32768: 1 (codes) + 1 (fp16 scale+zero per 32) on the
+    # packed part, 16 bits on the 128 ring tokens
+    cfg = _cfg(xq)
+    T, r = 32768, 128
+    expect = ((T - r) * (1.0 + 1.0) + r * 16.0) / T
+    assert abs(xq.equivalent_bits(cfg, True, T) - expect) < 1e-12
+    cfg4 = _cfg(xq, batch=8, n_kv_heads=8, group=64, vq=0)     # K 2-bit, V 1-bit, g = 64, shared
+    assert xq.equivalent_bits(cfg4) == 0.75
+    expect4 = ((T - r) * (0.75 + 0.5) + r * 16.0) / T
+    assert abs(xq.equivalent_bits(cfg4, True, T) - expect4) < 1e-12

@@ -1,0 +1,221 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+Packed words, metadata and ring contents are compared bit for bit; attention outputs to
+max-abs 2e-3."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_11236_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib_():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import xq_testlib as tl
+    return tl
+
+
+def _run_prefill_case(tl, w, T, slices=None, fused_too=True, tps_list=(0,)):
+    K, V = synth.kv_all(w, T)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=T + 4)
+    cache.quantize_pack(Kd, Vd)
+    q = synth.queries(w).cuda()
+    sigma = 1.0 / np.sqrt(w.head_dim)
+    outs = []
+    for tps in tps_list:
+        cache.set_tiles_per_split(tps)
+        outs.append(cache.decode_attention(q, sigma))
+        if fused_too:
+            outs.append(cache.decode_attention(q, sigma, flags=1))
+    torch.cuda.synchronize()
+    if slices is None:
+        slices = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    worst = 0.0
+    for bi, h in slices:
+        st = tl.oracle_slice(w, K, V, bi, h)
+        tl.check_stored(cache, w, st, bi, h)
+        tl.check_unpack(cache, w, st, bi, h)
+        ref = tl.oracle_attention(w, st, q, bi, h, sigma)
+        for o in outs:
+            worst = max(worst, tl.check_attention(o, w, ref, bi, h))
+    cache.close()
+    return worst
+
+
+def test_cfg0_tiny_pair(lib_):
+    w = synth.workloads()[0]
+    worst = _run_prefill_case(lib_, w, w.context, tps_list=(0, 1, 2))
+    print("cfg0 worst attention error", worst)
+
+
+@pytest.mark.parametrize("T", [1, 31, 32, 33, 64, 65, 96, 129, 300])
+def test_ragged_lengths_small(lib_, T):
+    """Empty packed part (T <= R), first group, ragged tiles: D = 64, g = 32, R = 32."""
+    w = synth.scaled(synth.workloads()[0], batch=2, n_q_heads=2, n_kv_heads=2)
+    _run_prefill_case(lib_, w, T)
+
+
+@pytest.mark.parametrize("g,R,kq,vq,km,vm,rep", [
+    (32, 128, 4, 4, 0, 0, 1),    # 2/2 bit, all pairs shared
+    (32, 128, 4, 4, 4, 4, 1),    # no sharing (baseline path)
+    (64, 128, 4, 0, 0, 0, 4),    # K 2-bit, V 1-bit, g 64, GQA 4:1, shared
+    (64, 64, 0, 4, 0, 4, 2),     # K 1-bit shared, V 2-bit unshared, GQA 2:1
+    (32, 64, 2, 2, 4, 2, 1),     # mixed widths: layers 0-1 2-bit, 2-3 1-bit; V shared from layer 2
+    (32, 32, 0, 0, 0, 0, 4),     # all 1-bit, shared, GQA 4:1
+])
+def test_d128_variants(lib_, g, R, kq, vq, km, vm, rep):
+    base = synth.workloads()[1]
+    w = synth.scaled(base, n_layers=4, batch=2, n_q_heads=2 * rep, n_kv_heads=2, group=g, residual=R,
+                     kq=kq, vq=vq, km=km, vm=vm, eta1=1 / 6, eta2=0.045, seed=11 + g + rep)
+    worst = _run_prefill_case(lib_, w, 1000, tps_list=(0, 1))
+    print("variant worst attention error", worst)
+
+
+def test_peaked_attention(lib_):
+    """Queries aligned with one cached key: few tokens carry the weight, the regime where
+    score errors show most."""
+    tl = lib_
+    base = synth.workloads()[1]
+    w = synth.scaled(base, n_layers=2, batch=1, n_q_heads=4, n_kv_heads=4, km=0, vm=0, eta1=1 / 6, eta2=0.045)
+    T = 2048
+    K, V = synth.kv_all(w, T)
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(K.cuda(), V.cuda())
+    q = synth.queries(w)
+    for h in range(4):
+        q[:, 0, h] = (K[:, 0, h, 100 + 300 * h].float() * (0.6 + 0.2 * h)).half()
+    sigma = 1.0 / np.sqrt(w.head_dim)
+    out = cache.decode_attention(q.cuda(), sigma)
+    out2 = cache.decode_attention(q.cuda(), sigma, flags=1)
+    for h in range(4):
+        st = tl.oracle_slice(w, K, V, 0, h)
+        ref = tl.oracle_attention(w, st, q, 0, h, sigma)
+        tl.check_attention(out, w, ref, 0, h)
+        tl.check_attention(out2, w, ref, 0, h)
+    cache.close()
+
+
+def test_append_equals_prefill(lib_):
+    """prefill(T0) + n appends == prefill(T0 + n): stored bytes bit for bit and attention,
+    across three ring flushes; checked against the oracle on the full history at several steps."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[0], batch=2, n_q_heads=2, n_kv_heads=2, residual=64)
+    T0, n = 150, 110
+    K, V = synth.kv_all(w, T0 + n)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=T0 + n)
+    cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    sigma = 0.125
+    q = synth.queries(w).cuda()
+    check_at = {1, 10, 11, 42, 43, 74, 75, 106, 107, n}
+    for i in range(1, n + 1):
+        t = T0 + i - 1
+        cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
+        if i in check_at:
+            out = cache.decode_attention(q, sigma)
+            for bi, h in [(0, 0), (1, 1)]:
+                st = tl.oracle_slice(w, K[:, :, :, :t + 1], V[:, :, :, :t + 1], bi, h)
+                tl.check_stored(cache, w, st, bi, h)
+                tl.check_attention(out, w, tl.oracle_attention(w, st, q, bi, h, sigma), bi, h)
+    # and against a fresh prefill of the whole history through the library itself
+    fresh = tl.make_cache(w, max_tokens=T0 + n)
+    fresh.quantize_pack(Kd, Vd)
+    for l in range(w.n_layers):
+        T, Tq = cache.length(l)
+        assert fresh.length(l) == (T, Tq)
+        for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+            a, b = cache.region(l, name), fresh.region(l, name)
+            if a is not None:
+                used = {"k_codes": Tq * 64 * 2 // 8, "v_codes": Tq * 64 * 2 // 8, "k_meta": (Tq // 32) * 64 * 4,
+                        "v_meta": Tq * 2 * 4}[name]
+                assert torch.equal(a[:, :used], b[:, :used]), (l, name)
+    assert torch.equal(cache.decode_attention(q, sigma), fresh.decode_attention(q, sigma))
+    cache.close()
+    fresh.close()
+
+
+def test_append_from_empty_and_capacity(lib_):
+    tl = lib_
+    from paper_2510_11236_amd import XqError
+    w = synth.scaled(synth.workloads()[0], batch=1, n_q_heads=1, n_kv_heads=1)
+    n = 70
+    K, V = synth.kv_all(w, n)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=n)
+    q = synth.queries(w).cuda()
+    with pytest.raises(XqError) as e:
+        cache.decode_attention(q, 0.125)
+    assert e.value.code == -4
+    for t in range(n):
+        cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
+    st = tl.oracle_slice(w, K, V, 0, 0)
+    tl.check_stored(cache, w, st, 0, 0)
+    out = cache.decode_attention(q, 0.125)
+    tl.check_attention(out, w, tl.oracle_attention(w, st, q, 0, 0, 0.125), 0, 0)
+    with pytest.raises(XqError) as e:
+        cache.append_token(Kd[:, :, :, 0].contiguous(), Vd[:, :, :, 0].contiguous())
+    assert e.value.code == -3
+    with pytest.raises(XqError) as e:
+        cache.quantize_pack(Kd, Vd)
+    assert e.value.code == -4
+    cache.reset()
+    with pytest.raises(XqError) as e:
+        cache.quantize_pack(torch.cat([Kd, Kd], 3), torch.cat([Vd, Vd], 3))
+    assert e.value.code == -3
+    cache.close()
+
+
+def test_degenerate_values(lib_):
+    """Constant groups, tiny and large magnitudes, exact ties."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[0], batch=1, n_q_heads=2, n_kv_heads=2, eta2=0.0)
+    T = 160
+    K, V = synth.kv_all(w, T)
+    K[:, :, :, 0:32, 5] = 1.25           # constant key group
+    V[:, :, :, 7, 0:32] = -0.5           # constant value group
+    K[:, :, 0, 32:64] *= 1e-4            # subnormal-range fp16
+    V[:, :, 1, 32:64] *= 300.0           # large values
+    K[0, 0, 0, 64:96, 9] = torch.tensor([0, 3] + [0.5, 1.5, 2.5] * 10, dtype=torch.float16)   # exact ties
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(K.cuda(), V.cuda())
+    q = synth.queries(w).cuda()
+    out = cache.decode_attention(q, 0.125)
+    for h in range(2):
+        st = tl.oracle_slice(w, K, V, 0, h)
+        tl.check_stored(cache, w, st, 0, h)
+        # outputs scale with |V| here, so the tolerance is relative to the largest value
+        ref = tl.oracle_attention(w, st, q, 0, h, 0.125)
+        scale = max(1.0, max(float(np.max(np.abs(r))) for r in ref.values()))
+        tl.check_attention(out, w, ref, 0, h, atol=tl.ATOL * scale)
+    cache.close()
+
+
+def test_strided_input_and_layer_ranges(lib_):
+    """Non-contiguous source (token stride > D) and per-layer-range calls."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[1], n_layers=4, batch=1, n_q_heads=2, n_kv_heads=2, km=0, vm=0,
+                     eta1=1 / 6, eta2=0.045)
+    T = 400
+    K, V = synth.kv_all(w, T)
+    big_k = torch.zeros(4, 1, 2, T, 256, dtype=torch.float16, device="cuda")
+    big_v = torch.zeros_like(big_k)
+    big_k[..., :128] = K.cuda()
+    big_v[..., :128] = V.cuda()
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(big_k[:2, ..., :128], big_v[:2, ..., :128], layer0=0)
+    cache.quantize_pack(big_k[2:, ..., :128], big_v[2:, ..., :128], layer0=2)
+    q = synth.queries(w).cuda()
+    sigma = 1 / np.sqrt(128)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    cache.decode_attention(q[:2].contiguous(), sigma, out=out[:2], layer0=0, flags=1)
+    cache.decode_attention(q[2:3].contiguous(), sigma, out=out[2:3], layer0=2)
+    cache.decode_attention(q[3:].contiguous(), sigma, out=out[3:], layer0=3)
+    for h in range(2):
+        st = tl.oracle_slice(w, K, V, 0, h)
+        tl.check_stored(cache, w, st, 0, h)
+        tl.check_attention(out, w, tl.oracle_attention(w, st, q, 0, h, sigma), 0, h)
+    cache.close()
