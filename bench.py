@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-KV decode hot path on one MI355X.
+
+A step = one decode step of the whole hot path for every layer: append one new token per
+sequence (with the ring flush when it falls due) and decode attention of one query per head
+over the packed cache + fp16 ring.  Inputs are synthetic, seeded, resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--schedule auto|sequential|fused]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(w, T, fused):
+    """HBM bytes one decode-attention pass over all layers must read: every packed code and
+    its fp16 scale/zero once per layer that uses it (once per pair when fused), the fp16 ring,
+    queries; plus the fp32 outputs written.  Split partials are workspace, not counted."""
+    g, R, D = w.group, w.residual, w.head_dim
+    over = T - R
+    Tq = 0 if over <= 0 else g * ((over + g - 1) // g)
+    r = T - Tq
+    nbh = w.batch * w.n_kv_heads
+    total = 0
+    for l in range(w.n_layers):
+        bk = 2 if l < w.kq else 1
+        bv = 2 if l < w.vq else 1
+        k_shared = not (l < w.km or l % 2 == 0)
+        v_shared = not (l < w.vm or l % 2 == 0)
+        k_codes = Tq * D * bk // 8
+        v_codes = Tq * D * bv // 8
+        if fused and k_shared:
+            k_codes = 0
+        if fused and v_shared:
+            v_codes = 0
+        meta = Tq * D * 4 // g * 2
+        ring = r * D * 2 * 2
+        total += nbh * (k_codes + v_codes + meta + ring)
+        total += w.batch * w.n_q_heads * D * (2 + 4)
+    return total
+
+
+def cpu_baseline(w, slices, q_cpu, sigma, T):
+    """Oracle decode (dequantize + attention) timed on host threads over a bounded sample."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import xq_oracle as orc
+    sch = orc.Schedule(w.n_layers, w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.group, w.residual)
+    rep = w.n_q_heads // w.n_kv_heads
+    jobs = []
+    for (bi, h), (K2, V2) in slices.items():
+        # a pair on its own is a 2-layer model with the pair's schedule
+        sch2 = orc.Schedule(2, 2 if w.kq > 0 else 0, 2 if w.vq > 0 else 0, 0 if w.km < w.n_layers else 2,
+                            0 if w.vm < w.n_layers else 2, w.eta1, w.eta2, w.group, w.residual)
+        st = orc.cache_slice(sch2, K2, V2)
+        for l in (0, 1):
+            jobs.append((sch2, st, l, q_cpu[l, bi, h * rep:(h + 1) * rep].numpy().view(np.uint16)))
+    threads = min(len(jobs), os.cpu_count() or 1, 16)
+
+    def run(j):
+        return orc.decode_slice(j[0], j[1], j[2], j[3], sigma)
+
+    run(jobs[0])
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(run, jobs))
+    dt = time.perf_counter() - t0
+    slice_layers_per_s = len(jobs) / dt
+    t_step = w.n_layers * w.batch * w.n_kv_heads / slice_layers_per_s
+    return {"value": w.batch * T / t_step, "unit": "KV tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(jobs)} (layer, sequence, kv-head) slices of the first layer pair at T={T}, "
+                      f"dequantize+attention in fp64, {dt:.1f} s wall, scaled linearly to all "
+                      f"{w.n_layers * w.batch * w.n_kv_heads} slices"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2)
+    ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "fused"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-slices", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (every (sequence, kv head) slice is independent; "
+              "see DESIGN.md 'How it would shard'); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2510_11236_amd import synth
+    from paper_2510_11236_amd.binding import XqCache, config_from_workload, equivalent_bits
+
+    w = synth.workloads()[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    n_extra = args.warmup + args.steps
+    T0 = w.context
+    cfg = config_from_workload(w, max_tokens=T0 + n_extra + 1)
+    cache = XqCache(cfg, dev)
+    sigma = 1.0 / float(np.sqrt(w.head_dim))
+
+    # ---- synthetic KV, packed layer pair by layer pair (also the pack measurement)
+    Ttot = T0 + n_extra
+    new_k = torch.empty((n_extra, w.n_layers, w.batch, w.n_kv_heads, w.head_dim), dtype=torch.float16, device=dev)
+    new_v = torch.empty_like(new_k)
+    sample = [(i % w.batch, (7 * i + 3) % w.n_kv_heads) for i in range(args.cpu_slices)]
+    slices = {}
+    pack_ms, pack_bytes = 0.0, 0
+    pend = []
+    for l, K, V in synth.kv_layers(w, Ttot, dev):
+        new_k[:, l] = K[:, :, T0:].permute(2, 0, 1, 3)
+        new_v[:, l] = V[:, :, T0:].permute(2, 0, 1, 3)
+        pend.append((K, V))
+        if l < 2 and not args.no_cpu_baseline:
+            for (bi, h) in sample:
+                kk, vv = K[bi, h, :T0].cpu().numpy().view(np.uint16), V[bi, h, :T0].cpu().numpy().view(np.uint16)
+                if l == 0:
+                    slices[(bi, h)] = ([kk], [vv])
+                else:
+                    slices[(bi, h)][0].append(kk)
+                    slices[(bi, h)][1].append(vv)
+        if len(pend) == 2 or l == w.n_layers - 1:
+            Kp = torch.stack([p[0][:, :, :T0] for p in pend], 0)
+            Vp = torch.stack([p[1][:, :, :T0] for p in pend], 0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            cache.quantize_pack(Kp, Vp, layer0=l + 1 - len(pend))
+            e1.record()
+            torch.cuda.synchronize()
+            pack_ms += e0.elapsed_time(e1)
+            pack_bytes += Kp.numel() * 2 * 2
+            del Kp, Vp
+            pend = []
+    del K, V
+    torch.cuda.empty_cache()
+    slices = {k: (np.stack(v[0]), np.stack(v[1])) for k, v in slices.items()}
+
+    # ---- choose the schedule
+    qs = [synth.queries(w, step, dev) for step in range(4)]
+    out = torch.empty(qs[0].shape, dtype=torch.float32, device=dev)
+
+    def time_decode(flags, n=5):
+        cache.decode_attention(qs[0], sigma, out=out, flags=flags)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            cache.decode_attention(qs[i % 4], sigma, out=out, flags=flags)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    can_fuse = any(l % 2 == 1 and l >= w.km and l >= w.vm for l in range(w.n_layers))
+    probe = {"sequential": time_decode(0)}
+    if can_fuse:
+        probe["fused"] = time_decode(1)
+    if args.schedule == "auto":
+        schedule = min(probe, key=probe.get)
+    else:
+        schedule = args.schedule if (args.schedule != "fused" or can_fuse) else "sequential"
+    flags = 1 if schedule == "fused" else 0
+
+    # ---- warmup + timed steps
+    def step(i, ev=None):
+        cache.append_token(new_k[i], new_v[i])
+        if ev is not None:
+            ev[0].record()
+        cache.decode_attention(qs[i % 4], sigma, out=out, flags=flags)
+        if ev is not None:
+            ev[1].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_begin.record()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    t_end.record()
+    torch.cuda.synchronize()
+    total_ms = t_begin.elapsed_time(t_end)
+    ms_per_step = total_ms / args.steps
+    decode_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    T_mid = T0 + args.warmup + (args.steps + 1) // 2
+    kv_tok_s = w.batch * T_mid / (ms_per_step * 1e-3)
+
+    alg = algorithmic_bytes(w, T_mid, fused=bool(flags))
+    achieved = alg / (decode_ms * 1e-3) / 1e9
+    res = {
+        "metric": "decode_attention_kv_tokens_per_s", "value": kv_tok_s, "unit": "KV tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_heads": w.n_q_heads,
+                   "kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "context": T0, "group": w.group,
+                   "residual": w.residual, "kq": w.kq, "vq": w.vq, "km": w.km, "vm": w.vm,
+                   "schedule": schedule, "step": "append 1 token/sequence + decode attention, all layers in one call"},
+        "roofline": {"bound": "hbm", "kernel": "xq_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms},
+        "decode_ms_by_schedule": probe,
+        "append_ms": ms_per_step - decode_ms,
+        "pack_GBps_fp16_read": pack_bytes / (pack_ms * 1e-3) / 1e9,
+        "equivalent_bits": {"paper_definition": equivalent_bits(cfg), "with_metadata_and_ring": equivalent_bits(cfg, True, T0)},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            res["roofline"]["traffic"] = json.load(open(traffic_file)).get(f"{w.name}:{schedule}")
+        except Exception:
+            pass
+    if not args.no_cpu_baseline:
+        q_cpu = qs[0].cpu()
+        res["cpu_baseline"] = cpu_baseline(w, slices, q_cpu, sigma, T0)
+    else:
+        res["cpu_baseline"] = None
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
