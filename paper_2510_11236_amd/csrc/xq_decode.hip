@@ -35,6 +35,19 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// acc + w * (fp16 in the low / high half of c), fp32 result: one v_fma_mix_f32 each.  Written
+// as instructions because the compiler, when several heads share one code register, converts
+// the halves to fp32 first and keeps them live, which costs an extra conversion per code and
+// hundreds of registers.
+__device__ __forceinline__ float fma_mix_lo(float w, uint32_t c, float acc) {
+    asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[0,1,0]" : "+v"(acc) : "v"(w), "v"(c));
+    return acc;
+}
+__device__ __forceinline__ float fma_mix_hi(float w, uint32_t c, float acc) {
+    asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(acc) : "v"(w), "v"(c));
+    return acc;
+}
+
 template <int W>
 __device__ __forceinline__ float group_sum(float v) {  // sum over aligned groups of W lanes
 #pragma unroll
@@ -150,18 +163,15 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     if (split < a.n_splits) {
         // ------------------------------------------------------------ packed tokens
         const int gi = lane / LPG, li = lane % LPG;  // key-weight prep role
-        float qk[NV][CPP], qz[NV][CPP];
+        float qz[NV][CPP];  // q * sm_scale * log2(e) for the channels this lane prepares
+        float pw[CPP];      // the code of channel c arrives as c * 2^((BK*c) mod 8 - 24); undo it in the weight
+#pragma unroll
+        for (int k = 0; k < CPP; ++k) pw[k] = __builtin_ldexpf(1.0f, 24 - ((BK * (li * CPP + k)) & 7));
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const uint16_t *qp = qptr(v);
 #pragma unroll
-            for (int k = 0; k < CPP; ++k) {
-                int c = li * CPP + k;
-                float qv = hbits(qp[c]) * a.scale_log2e;
-                qz[v][k] = qv;
-                // the code of channel c arrives as c * 2^((BK*c) mod 8 - 24)
-                qk[v][k] = qv * __builtin_ldexpf(1.0f, 24 - ((BK * c) & 7));
-            }
+            for (int k = 0; k < CPP; ++k) qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
         }
         const int tile_end = min((split + 1) * a.tiles_per_split, (n_blocks + 3) / 4);
         for (int tile = split * a.tiles_per_split + wave; tile < tile_end; tile += 4) {
@@ -184,15 +194,32 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     }
                 }
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    float zp = 0.f;
+                for (int y = 0; y < NLAY; ++y) {
+                    float sh[CPP], zh[CPP];
 #pragma unroll
                     for (int k = 0; k < CPP; ++k) {
-                        uint32_t m = meta[v / NREP][k];
-                        s_kw[wave][v][gi][li * CPP + k] = qk[v][k] * hbits(m & 0xffffu);
-                        zp = fmaf(qz[v][k], hbits(m >> 16), zp);
+                        sh[k] = hbits(meta[y][k] & 0xffffu) * pw[k];
+                        zh[k] = hbits(meta[y][k] >> 16);
                     }
-                    zs[v] = group_sum<LPG>(zp);
+#pragma unroll
+                    for (int n = 0; n < NREP; ++n) {
+                        const int v = y * NREP + n;
+                        float zp = 0.f;
+                        float wv[CPP];
+#pragma unroll
+                        for (int k = 0; k < CPP; ++k) {
+                            wv[k] = qz[v][k] * sh[k];
+                            zp = fmaf(qz[v][k], zh[k], zp);
+                        }
+#pragma unroll
+                        for (int k4 = 0; k4 < CPP; k4 += 4) {
+                            if constexpr (CPP >= 4)
+                                *(float4 *)&s_kw[wave][v][gi][li * CPP + k4] = make_float4(wv[k4], wv[k4 + 1], wv[k4 + 2], wv[k4 + 3]);
+                            else
+                                *(float2 *)&s_kw[wave][v][gi][li * CPP] = make_float2(wv[0], wv[1]);
+                        }
+                        zs[v] = group_sum<LPG>(zp);
+                    }
                 }
             }
             // ---- this lane's two key rows (tokens r16 and r16 + 16 of block blk)
@@ -248,35 +275,47 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int v = 0; v < NV; ++v) sc[s][v] = 0.f;
             const int kg = (row * 32) / G;  // key group of this row inside the tile
+            {
+                constexpr int CPB = BYTEK / 4;            // chunks of 4 positions per byte
+                constexpr int NCHUNK = WK * 2 * CPB;
+                constexpr int NSTEP = NCHUNK * NV;
+                constexpr int PF = NSTEP > 2 ? 2 : 1;
+                float4 wl[PF + 1], wh[PF + 1];
+                auto chunk_base = [](int ci) {  // first low-half channel of chunk ci
+                    return (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4;
+                };
+                auto issue = [&](int st) {
+                    const int base = chunk_base(st / NV);
+                    wl[st % (PF + 1)] = *(const float4 *)&s_kw[wave][st % NV][kg][base];
+                    wh[st % (PF + 1)] = *(const float4 *)&s_kw[wave][st % NV][kg][base + HALFK];
+                };
 #pragma unroll
-            for (int wi = 0; wi < WK; ++wi) {
+                for (int st = 0; st < PF; ++st) issue(st);
 #pragma unroll
-                for (int src = 0; src < 2; ++src) {
+                for (int ci = 0; ci < NCHUNK; ++ci) {
+                    const int wi = ci / (2 * CPB), src = (ci / CPB) % 2, p4 = (ci % CPB) * 4;
+                    uint32_t c2[2][4];
 #pragma unroll
-                    for (int p4 = 0; p4 < BYTEK; p4 += 4) {
-                        // channels [base, base+4) in the low halves, [base + HALFK, ..+4) in the high halves
-                        const int base = wi * PERK + src * BYTEK + p4;
-                        float wlo[NV][4], whi[NV][4];
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        const uint32_t x = src ? (kc[s2][wi] >> 8) : kc[s2][wi];
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) {
-                            float4 t0 = *(const float4 *)&s_kw[wave][v][kg][base];
-                            float4 t1 = *(const float4 *)&s_kw[wave][v][kg][base + HALFK];
-                            wlo[v][0] = t0.x; wlo[v][1] = t0.y; wlo[v][2] = t0.z; wlo[v][3] = t0.w;
-                            whi[v][0] = t1.x; whi[v][1] = t1.y; whi[v][2] = t1.z; whi[v][3] = t1.w;
-                        }
+                        for (int p = 0; p < 4; ++p)
+                            c2[s2][p] = x & (MASKK << (BK * (p4 + p)));
+                    }
 #pragma unroll
-                        for (int s = 0; s < 2; ++s) {
-                            const uint32_t x = src ? (kc[s][wi] >> 8) : kc[s][wi];
+                    for (int v = 0; v < NV; ++v) {
+                        const int st = ci * NV + v;
+                        if (st + PF < NSTEP) issue(st + PF);
+                        const float4 lo = wl[st % (PF + 1)], hi = wh[st % (PF + 1)];
+                        const float wlo[4] = {lo.x, lo.y, lo.z, lo.w}, whi[4] = {hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-                            for (int p = 0; p < 4; ++p) {
-                                half2_t c2 = __builtin_bit_cast(half2_t, x & (MASKK << (BK * (p4 + p))));
+                        for (int p = 0; p < 4; ++p)
 #pragma unroll
-                                for (int v = 0; v < NV; ++v) {
-                                    sc[s][v] = fmaf(wlo[v][p], (float)c2.x, sc[s][v]);
-                                    sc[s][v] = fmaf(whi[v][p], (float)c2.y, sc[s][v]);
-                                }
+                            for (int s2 = 0; s2 < 2; ++s2) {
+                                sc[s2][v] = fma_mix_lo(wlo[p], c2[s2][p], sc[s2][v]);
+                                sc[s2][v] = fma_mix_hi(whi[p], c2[s2][p], sc[s2][v]);
                             }
-                        }
+                        if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
@@ -332,34 +371,44 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             wave_lds_fence();
             // ---- P . V^ over the packed codes
             const int jl = (lane * CPL) / G;  // channel group of this lane's channels
+            {
+                constexpr int VCH = (TPW / 2) / 4;        // chunks of 4 token pairs per word
+                constexpr int NCHUNK = 4 * WS * VCH;
+                constexpr int NSTEP = NCHUNK * NV;
+                constexpr int PF = NSTEP > 2 ? 2 : 1;
+                uint4 wq[PF + 1];
+                auto issue = [&](int st) {
+                    const int ci = st / NV;
+                    const int kb = ci / (WS * VCH), m = (ci / VCH) % WS, i0 = (ci % VCH) * 4;
+                    wq[st % (PF + 1)] = *(const uint4 *)&s_vw[wave][st % NV][kb][jl][m * TPW + 2 * i0];
+                };
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-                if (tile * 4 + kb >= n_blocks) break;  // wave-uniform
+                for (int st = 0; st < PF; ++st) issue(st);
 #pragma unroll
-                for (int m = 0; m < WS; ++m) {
+                for (int ci = 0; ci < NCHUNK; ++ci) {
+                    const int kb = ci / (WS * VCH), m = (ci / VCH) % WS, i0 = (ci % VCH) * 4;
+                    half2_t c2[4][CPL];
 #pragma unroll
-                    for (int i0 = 0; i0 < TPW / 2; i0 += 4) {
-                        half2_t w2[NV][4];
+                    for (int i = 0; i < 4; ++i)
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) {
-                            uint4 t = *(const uint4 *)&s_vw[wave][v][kb][jl][m * TPW + 2 * i0];
-                            w2[v][0] = __builtin_bit_cast(half2_t, t.x);
-                            w2[v][1] = __builtin_bit_cast(half2_t, t.y);
-                            w2[v][2] = __builtin_bit_cast(half2_t, t.z);
-                            w2[v][3] = __builtin_bit_cast(half2_t, t.w);
+                        for (int c = 0; c < CPL; ++c) {
+                            const int bit = BV * ((i0 + i) * CPL + c);   // position inside a half, < 16
+                            const uint32_t x = (bit >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                            c2[i][c] = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
                         }
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        const int st = ci * NV + v;
+                        if (st + PF < NSTEP) issue(st + PF);
+                        const uint4 t = wq[st % (PF + 1)];
+                        const half2_t w2[4] = {__builtin_bit_cast(half2_t, t.x), __builtin_bit_cast(half2_t, t.y),
+                                               __builtin_bit_cast(half2_t, t.z), __builtin_bit_cast(half2_t, t.w)};
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
 #pragma unroll
-                            for (int c = 0; c < CPL; ++c) {
-                                const int eh = (i0 + i) * CPL + c;      // code index inside a half
-                                const int bit = BV * eh;                 // < 16
-                                const uint32_t x = (bit >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
-                                half2_t c2 = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
-#pragma unroll
-                                for (int v = 0; v < NV; ++v)
-                                    accv[v][c] = __builtin_amdgcn_fdot2(w2[v][i], c2, accv[v][c], false);
-                            }
+                            for (int c = 0; c < CPL; ++c)
+                                accv[v][c] = __builtin_amdgcn_fdot2(w2[i], c2[i][c], accv[v][c], false);
+                        if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
