@@ -91,7 +91,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "fused"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-slices", type=int, default=4)
+    ap.add_argument("--cpu-slices", type=int, default=24)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (every (sequence, kv head) slice is independent; "
@@ -100,6 +102,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
 
     from paper_2510_11236_amd import synth
     from paper_2510_11236_amd.binding import XqCache, config_from_workload, equivalent_bits
@@ -165,14 +176,19 @@ def main():
         return e0.elapsed_time(e1) / n
 
     can_fuse = any(l % 2 == 1 and l >= w.km and l >= w.vm for l in range(w.n_layers))
-    probe = {"sequential": time_decode(0)}
+    probe = {"sequential": time_decode(0, 10)}
     if can_fuse:
-        probe["fused"] = time_decode(1)
+        probe["fused"] = time_decode(1, 10)
     if args.schedule == "auto":
         schedule = min(probe, key=probe.get)
     else:
         schedule = args.schedule if (args.schedule != "fused" or can_fuse) else "sequential"
     flags = 1 if schedule == "fused" else 0
+    by_schedule = {}
+    for name, ms in probe.items():
+        ab = algorithmic_bytes(w, T0, fused=(name == "fused"))
+        by_schedule[name] = {"decode_ms": ms, "kv_tokens_per_s": w.batch * T0 / (ms * 1e-3),
+                             "algorithmic_GBps": ab / (ms * 1e-3) / 1e9, "hbm_frac": ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
     # ---- warmup + timed steps
     def step(i, ev=None):
@@ -212,7 +228,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "xq_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms},
-        "decode_ms_by_schedule": probe,
+        "decode_only_by_schedule": by_schedule,
         "append_ms": ms_per_step - decode_ms,
         "pack_GBps_fp16_read": pack_bytes / (pack_ms * 1e-3) / 1e9,
         "equivalent_bits": {"paper_definition": equivalent_bits(cfg), "with_metadata_and_ring": equivalent_bits(cfg, True, T0)},
