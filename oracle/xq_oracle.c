@@ -100,6 +100,10 @@ void xqo_quantize_group(const uint16_t *x, long stride, int g, int B, float eta,
         if (v < mn) mn = v;
         if (v > mx) mx = v;
     }
+    /* the sign of a zero minimum / maximum is not the paper's concern: taken as +0, so
+     * that the stored zero-point does not depend on the order of -0 and +0 in the group */
+    mn = mn + 0.0f;
+    mx = mx + 0.0f;
     int n = (1 << B) - 1;
     volatile float range = mx - mn;                         /* Eq. 1 */
     volatile float s = (mx == mn) ? 0.0f : range / (float)n;

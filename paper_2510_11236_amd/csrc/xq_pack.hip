@@ -114,6 +114,8 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
                     mx = fmaxf(mx, x);
                 }
             }
+            mn += 0.0f;  // a zero minimum or maximum is stored as +0
+            mx += 0.0f;
             uint32_t meta;
             float s = group_params(mn, mx, n, c1, c2, &meta);
             s_mn[tid] = mn;
@@ -166,6 +168,248 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Wave-per-tile pack kernel for D = 128 (the production shape).  One wave quantizes the keys
+// or the values of one token group: lane = channel pair, the g token rows stay in registers.
+//
+// Codes without a division per element.  The contract is c = rint(RN((x - mn) / s)) with ties
+// to even.  RN(d / s) is monotone in d, so c = [d >= D1] + [d >= D2] + [d >= D3] where Dk is
+// the smallest fp32 d whose rounded quotient reaches 0.5+, 1.5, 2.5+ (the "+" levels are the
+// next fp32 above, because an exact 0.5 / 2.5 rounds down to the even code).  RN(d / s)
+// reaches a level tau exactly when d / s lies above the midpoint m between tau and the fp32
+// below it, i.e. d > m * s.  m has 25 significant bits and s at most 24, so m * s is exact in
+// fp64 and is never itself an fp32 number (its odd part has >= 25 bits): no tie can occur at
+// the cut, and Dk = the first fp32 above m * s.  Three fp64 multiplies per group replace g
+// IEEE divisions, and the stored codes stay bit-identical to the division form.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+struct GroupQ {
+    float nmn;         // -min
+    float D1, D2, D3;  // code thresholds on d = x - min
+};
+
+__device__ __forceinline__ float first_float_above(double c) {  // c > 0, not an fp32 value
+    float f = (float)c;
+    if ((double)f < c) f = __uint_as_float(__float_as_uint(f) + 1u);
+    return f;
+}
+
+template <int B>
+__device__ __forceinline__ GroupQ group_quant(float mn, float mx, float c1, float c2, uint32_t *meta) {
+    constexpr int n = (1 << B) - 1;
+    mn += 0.0f;  // a zero minimum or maximum is stored as +0
+    mx += 0.0f;
+    const float s = group_params(mn, mx, n, c1, c2, meta);
+    GroupQ q;
+    q.nmn = -mn;
+    if (s == 0.0f) {
+        q.D1 = q.D2 = q.D3 = INFINITY;
+    } else {
+        const double sd = (double)s;
+        q.D1 = first_float_above(sd * 0x1.000001p-1);  // midpoint of 0.5 and the next fp32
+        if (B == 2) {
+            q.D2 = first_float_above(sd * 0x1.7fffffp0);  // midpoint below 1.5
+            q.D3 = first_float_above(sd * 0x1.400001p1);  // midpoint of 2.5 and the next fp32
+        } else {
+            q.D2 = q.D3 = INFINITY;
+        }
+    }
+    return q;
+}
+
+// p = (running min, running -max) as an fp16 pair; folds in the low / high half of x.
+__device__ __forceinline__ uint32_t minmax_lo(uint32_t p, uint32_t x) {
+    asm("v_pk_min_f16 %0, %0, %1 op_sel:[0,0] op_sel_hi:[1,0] neg_hi:[0,1]" : "+v"(p) : "v"(x));
+    return p;
+}
+__device__ __forceinline__ uint32_t minmax_hi(uint32_t p, uint32_t x) {
+    asm("v_pk_min_f16 %0, %0, %1 op_sel:[0,1] op_sel_hi:[1,1] neg_hi:[0,1]" : "+v"(p) : "v"(x));
+    return p;
+}
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
+    half2_t r = __builtin_elementwise_min(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b));
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ float pair_min(uint32_t p) { return half_bits_to_float(p & 0xffffu); }
+__device__ __forceinline__ float pair_max(uint32_t p) { return -half_bits_to_float(p >> 16); }
+
+// d = RN(x + nmn) for the low / high fp16 half of x: the fp32 subtraction of the contract.
+__device__ __forceinline__ float sub_lo(uint32_t x, float nmn) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(x), "v"(nmn));
+    return d;
+}
+__device__ __forceinline__ float sub_hi(uint32_t x, float nmn) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(x), "v"(nmn));
+    return d;
+}
+
+// w = (w << B) | code(d), the code counted from compares, carried in through VCC.
+template <int B>
+__device__ __forceinline__ uint32_t push_code(uint32_t w, float d, const GroupQ &q) {
+    if (B == 2) {
+        float t;
+        asm("v_cmp_ge_f32 vcc, %2, %4\n\t"
+            "v_cndmask_b32 %1, %3, %5, vcc\n\t"
+            "v_addc_co_u32 %0, vcc, %0, %0, vcc\n\t"
+            "v_cmp_ge_f32 vcc, %2, %1\n\t"
+            "v_addc_co_u32 %0, vcc, %0, %0, vcc"
+            : "+v"(w), "=&v"(t)
+            : "v"(d), "v"(q.D1), "v"(q.D2), "v"(q.D3)
+            : "vcc");
+    } else {
+        asm("v_cmp_ge_f32 vcc, %1, %2\n\t"
+            "v_addc_co_u32 %0, vcc, %0, %0, vcc"
+            : "+v"(w)
+            : "v"(d), "v"(q.D1)
+            : "vcc");
+    }
+    return w;
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_or(uint32_t x) {
+    return x | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+
+template <int G, int B>
+__device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
+                                               int lane, int bh, int dst_tok) {
+    constexpr int D = 128;
+    // ---- per-channel min / max down the g tokens (two channels per lane)
+    uint32_t pa = 0x7c007c00u, pb = 0x7c007c00u;  // (+inf, +inf)
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+        pa = minmax_lo(pa, rows[t]);
+        pb = minmax_hi(pb, rows[t]);
+    }
+    const float c1 = B == 2 ? a.c1_2 : a.c1_1, c2 = B == 2 ? a.c2_2 : a.c2_1;
+    uint32_t ma, mb;
+    const GroupQ qa = group_quant<B>(pair_min(pa), pair_max(pa), c1, c2, &ma);
+    const GroupQ qb = group_quant<B>(pair_min(pb), pair_max(pb), c1, c2, &mb);
+    uint32_t *mp = (uint32_t *)(a.arena + d.k_meta + (int64_t)bh * a.st.k_meta) + (int64_t)(dst_tok / G) * D + 2 * lane;
+    *(uint2 *)mp = make_uint2(ma, mb);
+    if (!d.k_store) return;
+    // ---- codes: a word holds 32/B channels of one token = LW lanes x (2 channels x B bits)
+    constexpr int LW = 16 / B;             // lanes per word
+    constexpr int W = D * B / 32;          // words per token row
+    constexpr int CW = 4;
+    uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + (int64_t)bh * (B == 2 ? a.st.k_codes2 : a.st.k_codes1));
+    const int wsel = lane / LW, lsel = lane % LW;
+    uint32_t keep = 0;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+        uint32_t nib = push_code<B>(0u, sub_hi(rows[t], qb.nmn), qb);
+        nib = push_code<B>(nib, sub_lo(rows[t], qa.nmn), qa);
+        uint32_t x = nib << (2 * B * lsel);
+        x = dpp_or<0xB1>(x);    // lanes ^ 1
+        x = dpp_or<0x4E>(x);    // lanes ^ 2
+        x = dpp_or<0x141>(x);   // mirror inside each 8 lanes
+        if (LW == 16) x = dpp_or<0x140>(x);  // mirror inside the 16-lane row
+        keep = (lsel == t % LW) ? x : keep;
+        if (t % LW == LW - 1) {  // lane (wsel, lsel) now holds word wsel of token t - LW + 1 + lsel
+            const int tok = dst_tok + t - (LW - 1) + lsel;
+            cp[(int64_t)(tok / 32) * 32 * W + (wsel / CW) * 32 * CW + (tok % 32) * CW + wsel % CW] = keep;
+        }
+    }
+}
+
+template <int G, int B>
+__device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
+                                                 int lane, int bh, int dst_tok, float4 *s_par) {
+    constexpr int D = 128, NJ = D / G, LPG = G / 2;  // lanes per channel group
+    const int j = lane / LPG, i = lane % LPG;
+    const float c1 = B == 2 ? a.c1_2 : a.c1_1, c2 = B == 2 ? a.c2_2 : a.c2_1;
+    uint32_t *mp = (uint32_t *)(a.arena + d.v_meta + (int64_t)bh * a.st.v_meta) + (int64_t)dst_tok * NJ;
+    // ---- per-token min / max along the g channels of a group: reduce over the LPG lanes, then
+    // lane i of the group keeps token (chunk * LPG + i), so each lane owns one group's parameters
+#pragma unroll
+    for (int c = 0; c < G / LPG; ++c) {
+        uint32_t mine = 0;
+#pragma unroll
+        for (int k = 0; k < LPG; ++k) {
+            const int t = c * LPG + k;
+            uint32_t p = minmax_hi(minmax_lo(0x7c007c00u, rows[t]), rows[t]);
+#pragma unroll
+            for (int o = 1; o < LPG; o <<= 1) p = pk_min(p, (uint32_t)__shfl_xor((int)p, o, 64));
+            mine = (i == k) ? p : mine;
+        }
+        uint32_t meta;
+        const GroupQ q = group_quant<B>(pair_min(mine), pair_max(mine), c1, c2, &meta);
+        const int t = c * LPG + i;
+        mp[t * NJ + j] = meta;
+        s_par[t * NJ + j] = make_float4(q.nmn, q.D1, q.D2, q.D3);
+    }
+    if (!d.v_store) return;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- codes: this lane's two channels over TPW tokens fill one word, highest token first
+    constexpr int TPW = 16 / B;   // tokens per word
+    constexpr int WS = 2 * B;     // words per 32-token block
+    uint32_t *cp = (uint32_t *)(a.arena + d.v_codes + (int64_t)bh * (B == 2 ? a.st.v_codes2 : a.st.v_codes1));
+#pragma unroll
+    for (int blk = 0; blk < G / 32; ++blk) {
+        uint32_t words[WS];
+#pragma unroll
+        for (int m = 0; m < WS; ++m) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int k = TPW - 1; k >= 0; --k) {
+                const int t = blk * 32 + m * TPW + k;
+                const float4 f = s_par[t * NJ + j];
+                GroupQ q;
+                q.nmn = f.x;
+                q.D1 = f.y;
+                q.D2 = f.z;
+                q.D3 = f.w;
+                w = push_code<B>(w, sub_hi(rows[t], q.nmn), q);
+                w = push_code<B>(w, sub_lo(rows[t], q.nmn), q);
+            }
+            words[m] = w;
+        }
+        uint32_t *wp = cp + (int64_t)(dst_tok / 32 + blk) * 64 * WS + lane * WS;
+        if (WS == 4) *(uint4 *)wp = make_uint4(words[0], words[1], words[2], words[3]);
+        else *(uint2 *)wp = make_uint2(words[0], words[1]);
+    }
+}
+
+// grid.x = 2 * token groups (even: keys, odd: values), grid.y = sequence * kv head, grid.z = layer
+template <int G>
+__global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
+    constexpr int D = 128;
+    __shared__ float4 s_par[G * (D / G)];
+    const int lane = threadIdx.x;
+    const int grp = blockIdx.x >> 1;
+    const bool is_v = blockIdx.x & 1;
+    const int bh = blockIdx.y, lz = blockIdx.z;
+    const XqLayerDesc d = a.layers[a.layer0 + lz];
+    const int bi = bh / a.n_kv_heads, hh = bh % a.n_kv_heads;
+    const int dst_tok = a.dst_tok0 + grp * G;
+    const uint16_t *src;
+    int64_t s_tok;
+    if (a.from_ring) {
+        src = (const uint16_t *)(a.arena + (is_v ? d.v_res : d.k_res) + (int64_t)bh * a.st.res) +
+              (int64_t)(a.src_tok0 + grp * G) * D;
+        s_tok = D;
+    } else {
+        src = (is_v ? a.v_src : a.k_src) + lz * a.s_layer + bi * a.s_batch + hh * a.s_head +
+              (int64_t)(a.src_tok0 + grp * G) * a.s_tok;
+        s_tok = a.s_tok;
+    }
+    uint32_t rows[G];
+#pragma unroll
+    for (int t = 0; t < G; ++t) rows[t] = *(const uint32_t *)(src + t * s_tok + 2 * lane);
+    if (!is_v) {
+        if (d.bk == 2) pack_keys_wave<G, 2>(a, d, rows, lane, bh, dst_tok);
+        else pack_keys_wave<G, 1>(a, d, rows, lane, bh, dst_tok);
+    } else {
+        if (d.bv == 2) pack_values_wave<G, 2>(a, d, rows, lane, bh, dst_tok, s_par);
+        else pack_values_wave<G, 1>(a, d, rows, lane, bh, dst_tok, s_par);
+    }
+}
+
 // Copies n_tok tokens into the fp16 rings (token index t -> slot t mod R), keys and values.
 __global__ __launch_bounds__(256) void xq_ring_write_kernel(XqRingArgs a) {
     const int bh = blockIdx.y, lz = blockIdx.z;
@@ -214,8 +458,9 @@ __global__ __launch_bounds__(256) void xq_unpack_kernel(XqUnpackArgs a) {
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s) {
     if (a.n_groups <= 0) return hipSuccess;
     dim3 grid(a.n_groups, a.batch * a.n_kv_heads, n_layers), block(256);
-    if (D == 128 && g == 32) xq_pack_kernel<128, 32><<<grid, block, 0, s>>>(a);
-    else if (D == 128 && g == 64) xq_pack_kernel<128, 64><<<grid, block, 0, s>>>(a);
+    dim3 wgrid(2 * a.n_groups, a.batch * a.n_kv_heads, n_layers), wblock(64);
+    if (D == 128 && g == 32) xq_pack_wave_kernel<32><<<wgrid, wblock, 0, s>>>(a);
+    else if (D == 128 && g == 64) xq_pack_wave_kernel<64><<<wgrid, wblock, 0, s>>>(a);
     else if (D == 64 && g == 32) xq_pack_kernel<64, 32><<<grid, block, 0, s>>>(a);
     else if (D == 64 && g == 64) xq_pack_kernel<64, 64><<<grid, block, 0, s>>>(a);
     else return hipErrorInvalidValue;

@@ -180,6 +180,9 @@ def test_degenerate_values(lib_):
     K[:, :, 0, 32:64] *= 1e-4            # subnormal-range fp16
     V[:, :, 1, 32:64] *= 300.0           # large values
     K[0, 0, 0, 64:96, 9] = torch.tensor([0, 3] + [0.5, 1.5, 2.5] * 10, dtype=torch.float16)   # exact ties
+    K[1, 0, 0, 64:96, 11] = torch.tensor([-0.0, 0.0] * 8 + [1.0, 0.25] * 8, dtype=torch.float16)  # min is -0 then +0
+    V[1, 0, 1, 70, 0:32] = torch.tensor([0.0, -0.0] * 16, dtype=torch.float16)                # all zeros of both signs
+    V[0, 0, 0, 71, 32:64] = torch.tensor([-0.0] * 31 + [-2.0], dtype=torch.float16)           # max is -0
     cache = tl.make_cache(w, max_tokens=T)
     cache.quantize_pack(K.cuda(), V.cuda())
     q = synth.queries(w).cuda()

@@ -99,6 +99,17 @@ def test_constant_group_exact(oracle, B, eta):
         assert np.all(codes * h2f(s) + h2f(z) == x.astype(np.float64))
 
 
+def test_zero_extremes_stored_as_plus_zero(oracle):
+    """A group whose minimum is a zero of either sign stores z^ = +0, whatever the order."""
+    for vals in ([-0.0, 0.0, 1.0], [0.0, -0.0, 1.0], [-0.0, -0.0, 2.0]):
+        x = np.array(vals + [0.5] * 29, np.float16)
+        codes, s, z = oracle.quantize_group(x, 2, 0.0)
+        assert z == 0x0000 and codes[0] == 0 and codes[1] == 0
+    x = np.array([0.0, -0.0] * 16, np.float16)
+    codes, s, z = oracle.quantize_group(x, 1, 1 / 6)
+    assert (s, z) == (0, 0) and not codes.any()
+
+
 def test_exact_levels_reconstruct(oracle):
     """Values already on the B-bit grid {mn + k*s} with fp16-exact s come back exactly."""
     rng = np.random.default_rng(5)
