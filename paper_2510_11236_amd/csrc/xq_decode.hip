@@ -122,8 +122,9 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 
     // per wave: key weights q * s^ (pre-scaled) and value weights p * s^ (pre-scaled, pair order);
     // the cross-wave combine at the end reuses the key-weight space
-    typedef float KwT[NV][NGT][D];
-    typedef _Float16 VwT[NV][4][NJ][32];
+    // (rows padded so that the 4 rows of a wave, which read different groups, hit different banks)
+    typedef float KwT[NV][NGT][D + 4];
+    typedef _Float16 VwT[NV][4][NJ][32 + 8];
     typedef float PartT[NV][D + 2];
     constexpr int KW_BYTES = 4 * (int)sizeof(KwT), PART_BYTES = 4 * (int)sizeof(PartT);
     __shared__ __attribute__((aligned(16))) char s_raw[(KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES) + 4 * sizeof(VwT)];
@@ -132,8 +133,24 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     PartT *s_part = (PartT *)s_raw;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int split = blockIdx.x, bh = blockIdx.y;
-    const int layer = a.layer0 + blockIdx.z * NLAY;
+    // 1-D grid, XCD-aware: workgroups go round-robin over the 8 XCDs by linear id, so the
+    // (equal-sized) packed-token workgroups come first and the small ring workgroups last;
+    // interleaving the two kinds would hand some XCDs only ring work.
+    const int nbh = a.batch * a.n_kv_heads;
+    const int n_main = a.n_splits * nbh * (int)a.n_launch_z;
+    int split, bh, lz;
+    if ((int)blockIdx.x < n_main) {
+        split = blockIdx.x % a.n_splits;
+        const int rest = blockIdx.x / a.n_splits;
+        bh = rest % nbh;
+        lz = rest / nbh;
+    } else {
+        const int rid = blockIdx.x - n_main;
+        split = a.n_splits;
+        bh = rid % nbh;
+        lz = rid / nbh;
+    }
+    const int layer = a.layer0 + lz * NLAY;
     const int bi = bh / a.n_kv_heads, hkv = bh % a.n_kv_heads;
     const int row = lane >> 4, r16 = lane & 15;
     const int n_blocks = a.Tq / 32;
@@ -144,7 +161,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 
     auto qptr = [&](int v) -> const uint16_t * {  // query of virtual head v
         int y = v / NREP, n = v % NREP;
-        return a.q + (((int64_t)(blockIdx.z * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) * D;
+        return a.q + (((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) * D;
     };
 
     float m_run[NV], l_run[NV];
@@ -167,14 +184,26 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
         float pw[CPP];      // the code of channel c arrives as c * 2^((BK*c) mod 8 - 24); undo it in the weight
 #pragma unroll
         for (int k = 0; k < CPP; ++k) pw[k] = __builtin_ldexpf(1.0f, 24 - ((BK * (li * CPP + k)) & 7));
+        // with few heads a second, pre-shifted copy of q saves a multiply per weight
+        constexpr bool QK_COPY = NV == 1;
+        float qk[QK_COPY ? NV : 1][CPP];
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const uint16_t *qp = qptr(v);
 #pragma unroll
-            for (int k = 0; k < CPP; ++k) qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
+            for (int k = 0; k < CPP; ++k) {
+                qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
+                if constexpr (QK_COPY) qk[v][k] = qz[v][k] * pw[k];
+            }
         }
-        const int tile_end = min((split + 1) * a.tiles_per_split, (n_blocks + 3) / 4);
-        for (int tile = split * a.tiles_per_split + wave; tile < tile_end; tile += 4) {
+        // Every workgroup starts at a different tile of its range (and wraps around): slices lie
+        // at large power-of-two strides, so workgroups marching in step from tile 0 would all
+        // hit the same memory channels at once.  Softmax accumulation does not care about order.
+        const int tile0 = split * a.tiles_per_split;
+        const int n_tiles = min(tile0 + a.tiles_per_split, (n_blocks + 3) / 4) - tile0;
+        const int rot = (int)((bh * 37u + lz * 11u) % (unsigned)n_tiles);
+        for (int it = wave; it < n_tiles; it += 4) {
+            const int tile = tile0 + (it + rot) % n_tiles;
             const int blk = tile * 4 + row;
             const bool row_ok = blk < n_blocks;
             // ---- key weights for the tile's groups -> LDS
@@ -198,7 +227,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     float sh[CPP], zh[CPP];
 #pragma unroll
                     for (int k = 0; k < CPP; ++k) {
-                        sh[k] = hbits(meta[y][k] & 0xffffu) * pw[k];
+                        sh[k] = hbits(meta[y][k] & 0xffffu);
+                        if constexpr (!QK_COPY) sh[k] *= pw[k];
                         zh[k] = hbits(meta[y][k] >> 16);
                     }
 #pragma unroll
@@ -208,7 +238,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         float wv[CPP];
 #pragma unroll
                         for (int k = 0; k < CPP; ++k) {
-                            wv[k] = qz[v][k] * sh[k];
+                            if constexpr (QK_COPY) wv[k] = qk[v][k] * sh[k];
+                            else wv[k] = qz[v][k] * sh[k];
                             zp = fmaf(qz[v][k], zh[k], zp);
                         }
 #pragma unroll
@@ -269,11 +300,11 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 }
             wave_lds_fence();
             // ---- q . K^ over the packed codes
-            float sc[2][NV];
+            float sc[2][NV], sch[2][NV];  // two chains per score: low-half and high-half channels
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int v = 0; v < NV; ++v) sc[s][v] = 0.f;
+                for (int v = 0; v < NV; ++v) sc[s][v] = sch[s][v] = 0.f;
             const int kg = (row * 32) / G;  // key group of this row inside the tile
             {
                 constexpr int CPB = BYTEK / 4;            // chunks of 4 positions per byte
@@ -313,7 +344,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                             for (int s2 = 0; s2 < 2; ++s2) {
                                 sc[s2][v] = fma_mix_lo(wlo[p], c2[s2][p], sc[s2][v]);
-                                sc[s2][v] = fma_mix_hi(whi[p], c2[s2][p], sc[s2][v]);
+                                sch[s2][v] = fma_mix_hi(whi[p], c2[s2][p], sch[s2][v]);
                             }
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
@@ -336,8 +367,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             float pr[2][NV];
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                float u0 = row_ok ? sc[0][v] + zs[v] : -INFINITY;
-                float u1 = row_ok ? sc[1][v] + zs[v] : -INFINITY;
+                float u0 = row_ok ? (sc[0][v] + sch[0][v]) + zs[v] : -INFINITY;
+                float u1 = row_ok ? (sc[1][v] + sch[1][v]) + zs[v] : -INFINITY;
                 float tmax = wave_max(fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]));
                 float m_new = fmaxf(m_run[v], tmax);
                 if (m_new > m_run[v]) {  // wave-uniform
@@ -360,13 +391,15 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 const int pos = (tau / TPW) * TPW + 2 * (tw % (TPW / 2)) + tw / (TPW / 2);  // pair order
                 const float tsc = __builtin_ldexpf(1.0f, 6 - ((BV * CPL * tw) & 7));
 #pragma unroll
-                for (int v = 0; v < NV; ++v)
+                for (int v = 0; v < NV; ++v) {
+                    const float pt = pr[s][v] * tsc;
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) {
                         uint32_t m = vm[v / NREP][s][j];
-                        s_vw[wave][v][row][j][pos] = (_Float16)(pr[s][v] * hbits(m & 0xffffu) * tsc);
+                        s_vw[wave][v][row][j][pos] = (_Float16)(pt * hbits(m & 0xffffu));
                         zacc[v][j] = fmaf(pr[s][v], hbits(m >> 16), zacc[v][j]);
                     }
+                }
             }
             wave_lds_fence();
             // ---- P . V^ over the packed codes
@@ -429,56 +462,96 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             for (int c = 0; c < CPL; ++c)
                 accv[v][c] = accv[v][c] * __builtin_ldexpf(1.0f, 18 - BV * c) + zsel;
         }
+        __syncthreads();  // every wave is done with the key weights before their space is reused
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) s_part[wave][v][lane * CPL + c] = accv[v][c];
+            if (lane == 0) {
+                s_part[wave][v][D] = m_run[v];
+                s_part[wave][v][D + 1] = l_run[v];
+            }
+        }
     } else {
         // ------------------------------------------------------------ fp16 ring (newest tokens)
-        float qf[NV][CPL];
+        // A 16-lane row takes one token per iteration (lane = D/16 channels), so a workgroup
+        // walks 16 ring tokens at a time; each row keeps its own softmax state.
+        constexpr int CR = D / 16;
+        float qf[NV][CR], acr[NV][CR];
 #pragma unroll
         for (int v = 0; v < NV; ++v)
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) qf[v][c] = hbits(qptr(v)[lane * CPL + c]) * a.scale_log2e;
+            for (int c = 0; c < CR; ++c) {
+                qf[v][c] = hbits(qptr(v)[r16 * CR + c]) * a.scale_log2e;
+                acr[v][c] = 0.f;
+            }
         const int r = a.T - a.Tq;
-        for (int i = wave; i < r; i += 4) {
+        for (int i = wave * 4 + row; i < r; i += 16) {
             const int slot = (a.Tq + i) % a.R;
 #pragma unroll
             for (int y = 0; y < NLAY; ++y) {
-                const uint16_t *kp = (const uint16_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + slot * D + lane * CPL;
-                const uint16_t *vp = (const uint16_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + slot * D + lane * CPL;
-                float kf[CPL], vf[CPL];
+                const uint32_t *kp = (const uint32_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2;
+                const uint32_t *vp = (const uint32_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2;
+                uint32_t kw[CR / 2], vw[CR / 2];
+                VecLoad<CR / 2>::ld(kp, kw);
+                VecLoad<CR / 2>::ld(vp, vw);
+                float kf[CR], vf[CR];
 #pragma unroll
-                for (int c = 0; c < CPL; ++c) {
-                    kf[c] = hbits(kp[c]);
-                    vf[c] = hbits(vp[c]);
+                for (int c = 0; c < CR; ++c) {
+                    kf[c] = hbits((c & 1) ? (kw[c / 2] >> 16) : (kw[c / 2] & 0xffffu));
+                    vf[c] = hbits((c & 1) ? (vw[c / 2] >> 16) : (vw[c / 2] & 0xffffu));
                 }
 #pragma unroll
                 for (int n = 0; n < NREP; ++n) {
                     const int v = y * NREP + n;
                     float part = 0.f;
 #pragma unroll
-                    for (int c = 0; c < CPL; ++c) part = fmaf(qf[v][c], kf[c], part);
-                    float u = group_sum<64>(part);
-                    float m_new = fmaxf(m_run[v], u);
-                    float alpha = exp2f(m_run[v] - m_new);
-                    float p = exp2f(u - m_new);
+                    for (int c = 0; c < CR; ++c) part = fmaf(qf[v][c], kf[c], part);
+                    const float u = group_sum<16>(part);
+                    const float m_new = fmaxf(m_run[v], u);
+                    const float alpha = exp2f(m_run[v] - m_new);
+                    const float p = exp2f(u - m_new);
                     l_run[v] = l_run[v] * alpha + p;
 #pragma unroll
-                    for (int c = 0; c < CPL; ++c) accv[v][c] = fmaf(p, vf[c], accv[v][c] * alpha);
+                    for (int c = 0; c < CR; ++c) acr[v][c] = fmaf(p, vf[c], acr[v][c] * alpha);
                     m_run[v] = m_new;
                 }
+            }
+        }
+        // merge the 4 rows of the wave
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            float M = fmaxf(m_run[v], __shfl_xor(m_run[v], 16, 64));
+            M = fmaxf(M, __shfl_xor(M, 32, 64));
+            const float f = (m_run[v] == -INFINITY) ? 0.f : exp2f(m_run[v] - M);
+            float l = l_run[v] * f;
+            l += __shfl_xor(l, 16, 64);
+            l += __shfl_xor(l, 32, 64);
+#pragma unroll
+            for (int c = 0; c < CR; ++c) {
+                float x = acr[v][c] * f;
+                x += __shfl_xor(x, 16, 64);
+                x += __shfl_xor(x, 32, 64);
+                acr[v][c] = x;
+            }
+            m_run[v] = M;
+            l_run[v] = l;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (row == 0) {
+#pragma unroll
+                for (int c = 0; c < CR; ++c) s_part[wave][v][r16 * CR + c] = acr[v][c];
+            }
+            if (lane == 0) {
+                s_part[wave][v][D] = m_run[v];
+                s_part[wave][v][D + 1] = l_run[v];
             }
         }
     }
 
     // ---------------------------------------------------------------- combine the 4 waves
-    __syncthreads();  // every wave is done with the key weights before their space is reused
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) s_part[wave][v][lane * CPL + c] = accv[v][c];
-        if (lane == 0) {
-            s_part[wave][v][D] = m_run[v];
-            s_part[wave][v][D + 1] = l_run[v];
-        }
-    }
     __syncthreads();
     for (int idx = tid; idx < NV * (D + 2); idx += 256) {
         const int v = idx / (D + 2), e = idx % (D + 2);
@@ -498,7 +571,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             }
         }
         const int y = v / NREP, n = v % NREP;
-        float *wp = a.ws + ((((int64_t)(blockIdx.z * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) *
+        float *wp = a.ws + ((((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) *
                                 (a.n_splits + 1) + split) * (D + 2);
         wp[e] = val;
     }
@@ -508,17 +581,18 @@ template <int NREP>
 hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipStream_t s) {
     constexpr int D = XQ_D, G = XQ_G, BK = XQ_BK, BV = XQ_BV;
     dim3 block(256);
+    XqDecodeArgs b = a;
+    b.n_launch_z = pair_fused ? n_layers / 2 : n_layers;
+    dim3 grid((unsigned)((a.n_splits + 1) * a.batch * a.n_kv_heads * b.n_launch_z));
     if (pair_fused) {
         // 2 * NREP virtual heads must fit the LDS weight tables
         if constexpr (2 * NREP * (XQ_TILE_TOKENS / G) <= 16 && (D == 128 || NREP == 1)) {
-            dim3 grid(a.n_splits + 1, a.batch * a.n_kv_heads, n_layers / 2);
-            xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(a);
+            xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(b);
         } else {
             return hipErrorInvalidValue;
         }
     } else {
-        dim3 grid(a.n_splits + 1, a.batch * a.n_kv_heads, n_layers);
-        xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(a);
+        xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(b);
     }
     return hipGetLastError();
 }

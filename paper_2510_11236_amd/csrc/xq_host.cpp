@@ -100,8 +100,11 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
     return (size_t)n_layers * c.batch * c.n_q_heads * (size_t)(n_splits + 1) * (c.head_dim + 2);
 }
 
-// Split plan: whole tiles of 128 tokens per split, at least one tile per wave of a
-// workgroup, enough workgroups to fill 256 CUs several times over, at most XQ_MAX_SPLITS.
+// Split plan: whole tiles of 128 tokens per split.  Few, long workgroups are cheapest (the
+// per-workgroup prologue, cross-wave combine and partial write are paid once), so the plan
+// takes the smallest number of splits that still gives about 4096 packed-token workgroups
+// (256 CUs x 4 resident workgroups x 4 rounds), at least one tile per wave, at most
+// XQ_MAX_SPLITS, and splits of equal size.
 void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int *tiles_per_split) {
     const xq_config &c = cache->cfg;
     int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
@@ -110,11 +113,18 @@ void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int
         *tiles_per_split = 4;
         return;
     }
-    int64_t units = (int64_t)tiles * c.batch * c.n_kv_heads * n_layers;
-    int tps = (int)((units + 8191) / 8192);
-    if (tps < 4) tps = 4;
-    if (tps > 32) tps = 32;
-    if (cache->tiles_per_split_override > 0) tps = cache->tiles_per_split_override;
+    int tps;
+    if (cache->tiles_per_split_override > 0) {
+        tps = cache->tiles_per_split_override;
+    } else {
+        int64_t slices = (int64_t)c.batch * c.n_kv_heads * n_layers;
+        int want = (int)((4096 + slices - 1) / slices);
+        int most = (tiles + 3) / 4;
+        if (want > most) want = most;
+        if (want > XQ_MAX_SPLITS) want = XQ_MAX_SPLITS;
+        if (want < 1) want = 1;
+        tps = (tiles + want - 1) / want;
+    }
     int min_tps = (tiles + XQ_MAX_SPLITS - 1) / XQ_MAX_SPLITS;
     if (tps < min_tps) tps = min_tps;
     *tiles_per_split = tps;

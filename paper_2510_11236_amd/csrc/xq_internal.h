@@ -88,6 +88,7 @@ struct XqDecodeArgs {
     float *out;         // [n_layers][b][h_q][D]
     float *ws;          // partials: [n_layers][b][h_q][n_splits + 1][D + 2]
     float scale_log2e;  // sm_scale * log2(e)
+    int32_t n_launch_z;  // layers (or layer pairs) in this launch; set by the launcher
 };
 // bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs
 hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv, int n_rep,

@@ -226,9 +226,10 @@ __device__ __forceinline__ uint32_t minmax_hi(uint32_t p, uint32_t x) {
     asm("v_pk_min_f16 %0, %0, %1 op_sel:[0,1] op_sel_hi:[1,1] neg_hi:[0,1]" : "+v"(p) : "v"(x));
     return p;
 }
-__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
-    half2_t r = __builtin_elementwise_min(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b));
-    return __builtin_bit_cast(uint32_t, r);
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {  // no NaNs here: one instruction
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 __device__ __forceinline__ float pair_min(uint32_t p) { return half_bits_to_float(p & 0xffffu); }
 __device__ __forceinline__ float pair_max(uint32_t p) { return -half_bits_to_float(p >> 16); }
@@ -297,21 +298,33 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     constexpr int CW = 4;
     uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + (int64_t)bh * (B == 2 ? a.st.k_codes2 : a.st.k_codes1));
     const int wsel = lane / LW, lsel = lane % LW;
-    uint32_t keep = 0;
+    // batches of LW rows: the OR trees of a batch run side by side, so that no instruction
+    // waits on the DPP read-after-write hazard of its own row
 #pragma unroll
-    for (int t = 0; t < G; ++t) {
-        uint32_t nib = push_code<B>(0u, sub_hi(rows[t], qb.nmn), qb);
-        nib = push_code<B>(nib, sub_lo(rows[t], qa.nmn), qa);
-        uint32_t x = nib << (2 * B * lsel);
-        x = dpp_or<0xB1>(x);    // lanes ^ 1
-        x = dpp_or<0x4E>(x);    // lanes ^ 2
-        x = dpp_or<0x141>(x);   // mirror inside each 8 lanes
-        if (LW == 16) x = dpp_or<0x140>(x);  // mirror inside the 16-lane row
-        keep = (lsel == t % LW) ? x : keep;
-        if (t % LW == LW - 1) {  // lane (wsel, lsel) now holds word wsel of token t - LW + 1 + lsel
-            const int tok = dst_tok + t - (LW - 1) + lsel;
-            cp[(int64_t)(tok / 32) * 32 * W + (wsel / CW) * 32 * CW + (tok % 32) * CW + wsel % CW] = keep;
+    for (int t0 = 0; t0 < G; t0 += LW) {
+        uint32_t x[LW];
+#pragma unroll
+        for (int k = 0; k < LW; ++k) {
+            uint32_t nib = push_code<B>(0u, sub_hi(rows[t0 + k], qb.nmn), qb);
+            nib = push_code<B>(nib, sub_lo(rows[t0 + k], qa.nmn), qa);
+            x[k] = nib << (2 * B * lsel);
         }
+#pragma unroll
+        for (int k = 0; k < LW; ++k) x[k] = dpp_or<0xB1>(x[k]);    // lanes ^ 1
+#pragma unroll
+        for (int k = 0; k < LW; ++k) x[k] = dpp_or<0x4E>(x[k]);    // lanes ^ 2
+#pragma unroll
+        for (int k = 0; k < LW; ++k) x[k] = dpp_or<0x141>(x[k]);   // mirror inside each 8 lanes
+        if (LW == 16) {
+#pragma unroll
+            for (int k = 0; k < LW; ++k) x[k] = dpp_or<0x140>(x[k]);  // mirror inside the 16-lane row
+        }
+        uint32_t keep = x[0];
+#pragma unroll
+        for (int k = 1; k < LW; ++k) keep = (lsel == k) ? x[k] : keep;
+        // lane (wsel, lsel) holds word wsel of token t0 + lsel
+        const int tok = dst_tok + t0 + lsel;
+        cp[(int64_t)(tok / 32) * 32 * W + (wsel / CW) * 32 * CW + (tok % 32) * CW + wsel % CW] = keep;
     }
 }
 
@@ -375,14 +388,16 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
     }
 }
 
-// grid.x = 2 * token groups (even: keys, odd: values), grid.y = sequence * kv head, grid.z = layer
+// grid.x = 2 * token groups (first half: keys, second half: values -- kept apart because
+// workgroups are dealt round-robin to the 8 XCDs and the two kinds cost differently),
+// grid.y = sequence * kv head, grid.z = layer
 template <int G>
 __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
     constexpr int D = 128;
     __shared__ float4 s_par[G * (D / G)];
     const int lane = threadIdx.x;
-    const int grp = blockIdx.x >> 1;
-    const bool is_v = blockIdx.x & 1;
+    const bool is_v = (int)blockIdx.x >= a.n_groups;
+    const int grp = is_v ? blockIdx.x - a.n_groups : blockIdx.x;
     const int bh = blockIdx.y, lz = blockIdx.z;
     const XqLayerDesc d = a.layers[a.layer0 + lz];
     const int bi = bh / a.n_kv_heads, hh = bh % a.n_kv_heads;
