@@ -165,7 +165,8 @@ def main():
     out = torch.empty(qs[0].shape, dtype=torch.float32, device=dev)
 
     def time_decode(flags, n=5):
-        cache.decode_attention(qs[0], sigma, out=out, flags=flags)
+        for i in range(3):
+            cache.decode_attention(qs[i], sigma, out=out, flags=flags)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -175,7 +176,7 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    can_fuse = any(l % 2 == 1 and l >= w.km and l >= w.vm for l in range(w.n_layers))
+    can_fuse = any(l % 2 == 1 and (l >= w.km or l >= w.vm) for l in range(w.n_layers))
     probe = {"sequential": time_decode(0, 10)}
     if can_fuse:
         probe["fused"] = time_decode(1, 10)

@@ -98,8 +98,12 @@ struct Partial {
     static constexpr int EXTRA = 2;
 };
 
-template <int D, int G, int BK, int BV, int NREP, int NLAY>
+// KSH / VSH: the NLAY layers of a workgroup read one key / value code tensor (a sharing pair);
+// when false each layer has its own codes and only the other tensor's unpacking is shared.
+template <int D, int G, int BK, int BV, int NREP, int NLAY, bool KSH = true, bool VSH = true>
 __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
+    constexpr int NKL = KSH ? 1 : NLAY;  // distinct key code tensors per workgroup
+    constexpr int NVL = VSH ? 1 : NLAY;
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane
     constexpr int NJ = D / G;             // value groups per token
@@ -254,34 +258,36 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 }
             }
             // ---- this lane's two key rows (tokens r16 and r16 + 16 of block blk)
-            uint32_t kc[2][WK];
-            {
-                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
+            uint32_t kc[NKL][2][WK];
+#pragma unroll
+            for (int y = 0; y < NKL; ++y) {
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[y].k_codes +
                                                         (int64_t)bh * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
                                      (int64_t)blk * 32 * WK;
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch) {
-                        if (row_ok) VecLoad<CWK>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
+                        if (row_ok) VecLoad<CWK>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[y][s][ch * CWK]);
                         else {
 #pragma unroll
-                            for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
+                            for (int w = 0; w < CWK; ++w) kc[y][s][ch * CWK + w] = 0;
                         }
                     }
             }
             // ---- value codes of the tile for this lane's channels, value metadata of its two tokens
-            uint32_t vc[4][WS];
-            {
-                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
+            uint32_t vc[NVL][4][WS];
+#pragma unroll
+            for (int y = 0; y < NVL; ++y) {
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[y].v_codes +
                                                         (int64_t)bh * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
                     const int b2 = tile * 4 + kb;
-                    if (b2 < n_blocks) VecLoad<WS>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[kb]);
+                    if (b2 < n_blocks) VecLoad<WS>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[y][kb]);
                     else {
 #pragma unroll
-                        for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
+                        for (int w = 0; w < WS; ++w) vc[y][kb][w] = 0;
                     }
                 }
             }
@@ -325,14 +331,16 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int ci = 0; ci < NCHUNK; ++ci) {
                     const int wi = ci / (2 * CPB), src = (ci / CPB) % 2, p4 = (ci % CPB) * 4;
-                    uint32_t c2[2][4];
+                    uint32_t c2[NKL][2][4];
 #pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        const uint32_t x = src ? (kc[s2][wi] >> 8) : kc[s2][wi];
+                    for (int y = 0; y < NKL; ++y)
 #pragma unroll
-                        for (int p = 0; p < 4; ++p)
-                            c2[s2][p] = x & (MASKK << (BK * (p4 + p)));
-                    }
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            const uint32_t x = src ? (kc[y][s2][wi] >> 8) : kc[y][s2][wi];
+#pragma unroll
+                            for (int p = 0; p < 4; ++p)
+                                c2[y][s2][p] = x & (MASKK << (BK * (p4 + p)));
+                        }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
                         const int st = ci * NV + v;
@@ -343,8 +351,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         for (int p = 0; p < 4; ++p)
 #pragma unroll
                             for (int s2 = 0; s2 < 2; ++s2) {
-                                sc[s2][v] = fma_mix_lo(wlo[p], c2[s2][p], sc[s2][v]);
-                                sch[s2][v] = fma_mix_hi(whi[p], c2[s2][p], sch[s2][v]);
+                                sc[s2][v] = fma_mix_lo(wlo[p], c2[KSH ? 0 : v / NREP][s2][p], sc[s2][v]);
+                                sch[s2][v] = fma_mix_hi(whi[p], c2[KSH ? 0 : v / NREP][s2][p], sch[s2][v]);
                             }
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
@@ -420,15 +428,17 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int ci = 0; ci < NCHUNK; ++ci) {
                     const int kb = ci / (WS * VCH), m = (ci / VCH) % WS, i0 = (ci % VCH) * 4;
-                    half2_t c2[4][CPL];
+                    half2_t c2[NVL][4][CPL];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int y = 0; y < NVL; ++y)
 #pragma unroll
-                        for (int c = 0; c < CPL; ++c) {
-                            const int bit = BV * ((i0 + i) * CPL + c);   // position inside a half, < 16
-                            const uint32_t x = (bit >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
-                            c2[i][c] = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
-                        }
+                        for (int i = 0; i < 4; ++i)
+#pragma unroll
+                            for (int c = 0; c < CPL; ++c) {
+                                const int bit = BV * ((i0 + i) * CPL + c);   // position inside a half, < 16
+                                const uint32_t x = (bit >= 8) ? (vc[y][kb][m] >> 8) : vc[y][kb][m];
+                                c2[y][i][c] = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
+                            }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
                         const int st = ci * NV + v;
@@ -440,7 +450,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         for (int i = 0; i < 4; ++i)
 #pragma unroll
                             for (int c = 0; c < CPL; ++c)
-                                accv[v][c] = __builtin_amdgcn_fdot2(w2[i], c2[i][c], accv[v][c], false);
+                                accv[v][c] = __builtin_amdgcn_fdot2(w2[i], c2[VSH ? 0 : v / NREP][i][c], accv[v][c], false);
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -585,9 +595,13 @@ hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipSt
     b.n_launch_z = pair_fused ? n_layers / 2 : n_layers;
     dim3 grid((unsigned)((a.n_splits + 1) * a.batch * a.n_kv_heads * b.n_launch_z));
     if (pair_fused) {
+        // pair_fused bits: 1 = keys shared, 2 = values shared.
         // 2 * NREP virtual heads must fit the LDS weight tables
         if constexpr (2 * NREP * (XQ_TILE_TOKENS / G) <= 16 && (D == 128 || NREP == 1)) {
-            xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(b);
+            if (pair_fused == 3) xq_decode_kernel<D, G, BK, BV, NREP, 2, true, true><<<grid, block, 0, s>>>(b);
+            else if (pair_fused == 2) xq_decode_kernel<D, G, BK, BV, NREP, 2, false, true><<<grid, block, 0, s>>>(b);
+            else if (pair_fused == 1) xq_decode_kernel<D, G, BK, BV, NREP, 2, true, false><<<grid, block, 0, s>>>(b);
+            else return hipErrorInvalidValue;
         } else {
             return hipErrorInvalidValue;
         }

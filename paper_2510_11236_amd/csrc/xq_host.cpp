@@ -378,20 +378,24 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
     int l = layer0;
     while (l < layer0 + n_layers) {
         const XqLayerDesc &d0 = cache->layers[l];
-        auto fusable = [&](int a) {  // pair (a, a+1) inside the range sharing keys and values
-            return (flags & XQ_DECODE_PAIR_FUSED) && xq_decode_can_fuse(c.head_dim, c.group, rep) && a % 2 == 0 && a + 1 < layer0 + n_layers &&
-                   !cache->layers[a + 1].k_store && !cache->layers[a + 1].v_store;
+        // sharing mode of the pair (a, a+1) when one workgroup may serve it: bit 0 keys shared,
+        // bit 1 values shared; 0 = not fusable
+        auto fuse_mode = [&](int a) -> int {
+            if (!(flags & XQ_DECODE_PAIR_FUSED) || !xq_decode_can_fuse(c.head_dim, c.group, rep)) return 0;
+            if (a % 2 != 0 || a + 1 >= layer0 + n_layers) return 0;
+            if (cache->layers[a + 1].bk != cache->layers[a].bk || cache->layers[a + 1].bv != cache->layers[a].bv) return 0;
+            return (cache->layers[a + 1].k_store ? 0 : 1) | (cache->layers[a + 1].v_store ? 0 : 2);
         };
-        const bool fused = fusable(l);
+        const int fused = fuse_mode(l);
         int e = l;
         while (e < layer0 + n_layers) {
             const XqLayerDesc &d = cache->layers[e];
             if (d.bk != d0.bk || d.bv != d0.bv) break;
             if (fused) {
-                if (!fusable(e)) break;
+                if (fuse_mode(e) != fused) break;
                 e += 2;
             } else {
-                if (fusable(e)) break;
+                if (fuse_mode(e)) break;
                 e += 1;
             }
         }
@@ -413,7 +417,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.out = (float *)out_f32 + (int64_t)(l - layer0) * per_layer_q;
         a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
-        if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, rep, e - l, fused ? 1 : 0, s) != hipSuccess)
+        if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, rep, e - l, fused, s) != hipSuccess)
             return XQ_ERR_HIP;
         l = e;
     }

@@ -49,6 +49,10 @@ def workloads():
         Workload("cfg3_gqa8b_32k_b8_k2v1_g64", 32, 8, 32, 8, 128, 32768, 64, 128, 32, 0, 0, 0, 1.0 / 6.0, 0.045, 3),
         Workload("cfg4_13b_16k_b16_prefill_decode64", 40, 16, 40, 40, 128, 16384, 32, 128, 40, 40, 0, 0,
                  1.0 / 6.0, 0.045, 4, decode_steps=64),
+        # not one of the five measured configurations: the schedule of the paper's main experiments
+        # (configuration table: kq=30, vq=2, km=32, vm=16 -> 1.375 equivalent bits) on the 7B shape
+        Workload("paper_main_schedule_7b_32k_b4", 32, 4, 32, 32, 128, 32768, 32, 128, 30, 2, 32, 16,
+                 1.0 / 6.0, 0.045, 5),
     ]
 
 

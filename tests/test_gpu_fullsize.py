@@ -107,6 +107,73 @@ def _run_full(tl, w, n_append, check_steps, sample_pairs, sample_bh):
     return worst
 
 
+def _run_full_mixed(tl, w, sample_layers, sample_bh):
+    """Like _run_full but with the oracle run on whole sampled slices (all layers of a slice are
+    needed because the schedule differs per layer)."""
+    from oracle import xq_oracle as orc
+    dev = "cuda:0"
+    T0 = w.context
+    cache = tl.make_cache(w, max_tokens=T0 + 1)
+    sigma = 1.0 / float(np.sqrt(w.head_dim))
+    new_k = torch.empty((w.n_layers, w.batch, w.n_kv_heads, w.head_dim), dtype=torch.float16, device=dev)
+    new_v = torch.empty_like(new_k)
+    layers = sorted({l for pr in sample_layers for l in pr})
+    hist = {bh: {} for bh in sample_bh}
+    pend = []
+    for l, K, V in synth.kv_layers(w, T0 + 1, dev):
+        new_k[l] = K[:, :, T0]
+        new_v[l] = V[:, :, T0]
+        pend.append((K, V))
+        if l in layers:
+            for (bi, h) in sample_bh:
+                hist[(bi, h)][l] = (K[bi, h].cpu().numpy().view(np.uint16), V[bi, h].cpu().numpy().view(np.uint16))
+        if len(pend) == 2:
+            cache.quantize_pack(torch.stack([p[0][:, :, :T0] for p in pend], 0),
+                                torch.stack([p[1][:, :, :T0] for p in pend], 0), layer0=l - 1)
+            pend = []
+    del K, V, pend
+    torch.cuda.empty_cache()
+    cache.append_token(new_k, new_v)
+    q = synth.queries(w, 1, dev)
+    outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1)]
+    torch.cuda.synchronize()
+    sch = tl.schedule_of(w)
+    rep = w.n_q_heads // w.n_kv_heads
+    worst = 0.0
+    for (bi, h), per_layer in hist.items():
+        bh = bi * w.n_kv_heads + h
+        for (l0, l1) in sample_layers:
+            # a two-layer oracle model with the pair's own widths and sharing
+            sch2 = orc.Schedule(2, 2 if sch.bits(l0, False) == 2 else 0, 2 if sch.bits(l0, True) == 2 else 0,
+                                2 if sch.stores(l1, False) else 0, 2 if sch.stores(l1, True) else 0,
+                                w.eta1, w.eta2, w.group, w.residual)
+            assert sch.bits(l0, False) == sch.bits(l1, False) and sch.bits(l0, True) == sch.bits(l1, True)
+            K2 = np.stack([per_layer[l0][0], per_layer[l1][0]])
+            V2 = np.stack([per_layer[l0][1], per_layer[l1][1]])
+            st = orc.cache_slice(sch2, K2, V2)
+            for y, l in enumerate((l0, l1)):
+                T, Tq = cache.length(l)
+                for is_v, pre in ((False, "k"), (True, "v")):
+                    B = st[y]["b" + pre]
+                    meta = cache.region(l, pre + "_meta")[bh].cpu().numpy().view(np.uint32)
+                    exp_meta = st[y][pre + "_scale"].astype(np.uint32).reshape(-1) | (st[y][pre + "_zero"].astype(np.uint32).reshape(-1) << 16)
+                    assert np.array_equal(meta[:exp_meta.size], exp_meta), (l, pre)
+                    if st[y][pre + "_codes"] is not None:
+                        words = cache.region(l, pre + "_codes")[bh].cpu().numpy().view(np.uint32)[:Tq * w.head_dim * B // 32]
+                        exp = (orc.pack_v_words if is_v else orc.pack_k_words)(st[y][pre + "_codes"], B)
+                        assert np.array_equal(words, exp), (l, pre)
+                    else:
+                        assert cache.region(l, pre + "_codes") is None
+                ref = orc.decode_slice(sch2, st, y, q[l, bi, h * rep:(h + 1) * rep].cpu().numpy().view(np.uint16), sigma)
+                for o in outs:
+                    err = float(np.max(np.abs(o[l, bi, h * rep:(h + 1) * rep].cpu().numpy() - ref)))
+                    worst = max(worst, err)
+                    assert err <= tl.ATOL, (l, bi, h, err)
+            print(f"  {w.name} layers {l0},{l1} slice ({bi},{h}) ok", flush=True)
+    cache.close()
+    return worst
+
+
 def test_cfg2_full_size(tl):
     w = synth.workloads()[2]
     worst = _run_full(tl, w, n_append=1, check_steps={1}, sample_pairs={0, 15},
@@ -135,3 +202,13 @@ def test_cfg4_prefill_pack_then_64_decode_steps(tl):
     worst = _run_full(tl, w, n_append=64, check_steps={1, 2, 33, 64}, sample_pairs={0, 19},
                       sample_bh=[(0, 0), (15, 39)])
     print("cfg4 full size worst attention error", worst)
+
+
+def test_paper_main_schedule_full_size(tl):
+    """kq=30, vq=2, km=32, vm=16 (the paper's main configuration, 1.375 equivalent bits): keys
+    never shared, values 1-bit and shared from layer 16 on; mixed bit widths inside one call and
+    value-only sharing in the fused schedule."""
+    w = synth.workloads()[5]
+
+    worst = _run_full_mixed(tl, w, sample_layers=[(0, 1), (14, 15), (16, 17), (30, 31)], sample_bh=[(0, 0), (3, 31)])
+    print("paper main schedule worst attention error", worst)
