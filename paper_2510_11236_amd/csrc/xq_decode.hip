@@ -275,35 +275,42 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         }
                     }
             }
-            // ---- value codes of the tile for this lane's channels, value metadata of its two tokens
+            // ---- value codes of the tile for this lane's channels, value metadata of its two tokens.
+            // With one head the loads are issued here, ahead of the key phase; with several heads
+            // they are issued after it, which keeps 32+ registers free during the key loop (one
+            // more wave per SIMD) at the cost of latency that the other waves cover.
+            constexpr bool V_LOAD_EARLY = NV == 1;
             uint32_t vc[NVL][4][WS];
-#pragma unroll
-            for (int y = 0; y < NVL; ++y) {
-                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[y].v_codes +
-                                                        (int64_t)bh * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
-#pragma unroll
-                for (int kb = 0; kb < 4; ++kb) {
-                    const int b2 = tile * 4 + kb;
-                    if (b2 < n_blocks) VecLoad<WS>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[y][kb]);
-                    else {
-#pragma unroll
-                        for (int w = 0; w < WS; ++w) vc[y][kb][w] = 0;
-                    }
-                }
-            }
             uint32_t vm[NLAY][2][NJ];
+            auto load_values = [&]() {
 #pragma unroll
-            for (int y = 0; y < NLAY; ++y)
+                for (int y = 0; y < NVL; ++y) {
+                    const uint32_t *cp = (const uint32_t *)(a.arena + dsc[y].v_codes +
+                                                            (int64_t)bh * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + (int64_t)bh * a.st.v_meta) +
-                                         ((int64_t)blk * 32 + r16 + 16 * s) * NJ;
-                    if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
-                    else {
+                    for (int kb = 0; kb < 4; ++kb) {
+                        const int b2 = tile * 4 + kb;
+                        if (b2 < n_blocks) VecLoad<WS>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[y][kb]);
+                        else {
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) vm[y][s][j] = 0;
+                            for (int w = 0; w < WS; ++w) vc[y][kb][w] = 0;
+                        }
                     }
                 }
+#pragma unroll
+                for (int y = 0; y < NLAY; ++y)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + (int64_t)bh * a.st.v_meta) +
+                                             ((int64_t)blk * 32 + r16 + 16 * s) * NJ;
+                        if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
+                        else {
+#pragma unroll
+                            for (int j = 0; j < NJ; ++j) vm[y][s][j] = 0;
+                        }
+                    }
+            };
+            if constexpr (V_LOAD_EARLY) load_values();
             wave_lds_fence();
             // ---- q . K^ over the packed codes
             float sc[2][NV], sch[2][NV];  // two chains per score: low-half and high-half channels
@@ -316,7 +323,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 constexpr int CPB = BYTEK / 4;            // chunks of 4 positions per byte
                 constexpr int NCHUNK = WK * 2 * CPB;
                 constexpr int NSTEP = NCHUNK * NV;
-                constexpr int PF = NSTEP > 2 ? 2 : 1;
+                constexpr int PF = (NSTEP > 2 && NV != 2) ? 2 : 1;  // NV == 2: one step ahead keeps the kernel at 128 registers
                 float4 wl[PF + 1], wh[PF + 1];
                 auto chunk_base = [](int ci) {  // first low-half channel of chunk ci
                     return (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4;
@@ -358,6 +365,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     }
                 }
             }
+            if constexpr (!V_LOAD_EARLY) load_values();
             // ---- online softmax bookkeeping (log2 domain), value weights -> LDS
             // The value weights p * s^ travel as fp16.  A token whose largest value scale is
             // >= 2^9 raises the softmax reference by the excess exponent, which keeps every
