@@ -88,9 +88,24 @@ typedef struct xq_config {
     int32_t residual;    /* R: multiple of g, g <= R <= 1024 */
     int32_t max_tokens;  /* capacity per sequence */
     int32_t kq, vq;      /* layers [0, kq) hold 2-bit key codes, the others 1-bit; vq likewise for values */
-    int32_t km, vm;      /* layers >= km (vm): the odd layer of each pair reuses the codes of the layer below */
+    int32_t km, vm;      /* layers >= km (vm) share codes: layer l reads the codes of layer G*(l/G) + k
+                          * (for the default G = 2, k = 0: the odd layer reads those of the layer below);
+                          * layers below km (vm), and a trailing group without its layer k, keep their own */
     float eta1, eta2;    /* calibration parameter for 1-bit / 2-bit groups, in [0, 0.5) */
+    /* Cross-layer compression variants of the ablations (Sec. 4.3 "Group Size", "Cross-Layer
+     * Compression Method", Appendix E).  All zero = the accelerated pair sharing used in every
+     * main experiment (G = 2, first layer dominant, gamma_0 = 1). */
+    int32_t share_group;     /* G: 0 (= 2), 2, 3 or 4 consecutive layers share one code tensor */
+    int32_t share_dominant;  /* k in [0, G): the layer of each group whose codes are stored */
+    int32_t merge_mode;      /* XQ_MERGE_*: how the stored codes of a pair are formed (G = 2, k = 0 only) */
+    float gamma0;            /* weight of the first layer's codes for XQ_MERGE_ROUND, in [0, 1] */
 } xq_config;
+
+/* merge_mode: stored codes e_m of a sharing pair from the two layers' own codes e_0, e_1 */
+#define XQ_MERGE_NONE  0   /* e_m = e_0 (Sec. 3.3.4) */
+#define XQ_MERGE_ROUND 1   /* e_m = floor(gamma0 e_0 + (1 - gamma0) e_1 + 1/2)  (Appendix E) */
+#define XQ_MERGE_FLOOR 2   /* e_m = floor((e_0 + e_1) / 2) */
+#define XQ_MERGE_CEIL  3   /* e_m = ceil((e_0 + e_1) / 2) */
 
 typedef struct xq_cache xq_cache; /* opaque host handle */
 
@@ -117,7 +132,10 @@ int xq_cache_len(const xq_cache *cache, int32_t layer, int32_t *T, int32_t *T_q)
  * k_f16, v_f16: device fp16, element (l, i, h, t, d) at
  *   base + l*strides[0] + i*strides[1] + h*strides[2] + t*strides[3] + d   (in elements),
  * l relative to layer0.  The layers must be empty (XQ_ERR_STATE otherwise); T <= max_tokens.
- * Writes codes (code-storing layers), metadata and the fp16 ring; sets the lengths to T. */
+ * Writes codes (code-storing layers), metadata and the fp16 ring; sets the lengths to T.
+ * With a merge_mode other than XQ_MERGE_NONE the range must contain both layers of every
+ * sharing pair it touches (the stored codes need both), else XQ_ERR_INVALID_ARG; the same
+ * holds for xq_append_token. */
 int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
                      const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream);
 

@@ -244,6 +244,28 @@ void xqo_pack_v_words(const uint8_t *codes, int Tq, int D, int B, uint32_t *word
         }
 }
 
+/* ------------------------------------------------ merged codes of a pair (Appendix E)
+ * e0, e1: the two layers' own B-bit codes at the same positions (e0 = first layer, weight
+ * gamma0).  mode 1: e_m = round-to-nearest(gamma0 e0 + (1 - gamma0) e1), computed as
+ * floor(x + 1/2) (the paper leaves the boundary values of gamma0, where x is an exact half,
+ * out of its six intervals).  mode 2 / 3: gamma0 = 1/2 with floor / ceil (the "Flooring" and
+ * "Ceiling" rows of the ablation table).  mode 0: e_m = e0 (Sec. 3.3.4). */
+void xqo_merge_codes(const uint8_t *e0, const uint8_t *e1, long count, int B, int mode, float gamma0,
+                     uint8_t *out) {
+    int n = (1 << B) - 1;
+    for (long i = 0; i < count; ++i) {
+        double x;
+        if (mode == 1) x = floor((double)gamma0 * e0[i] + (1.0 - (double)gamma0) * e1[i] + 0.5);
+        else if (mode == 2) x = floor(0.5 * e0[i] + 0.5 * e1[i]);
+        else if (mode == 3) x = ceil(0.5 * e0[i] + 0.5 * e1[i]);
+        else x = e0[i];
+        int em = (int)x;
+        if (em < 0) em = 0;
+        if (em > n) em = n;
+        out[i] = (uint8_t)em;
+    }
+}
+
 /* --------------------------------------------------- equivalent bit-width (App. C)
  * Codes only (metadata and the fp16 window are excluded, as the appendix says):
  * a layer below q holds 2-bit codes, else 1-bit; a layer stores codes iff it is

@@ -48,6 +48,8 @@ def lib():
         for f in (L.xqo_pack_k_words, L.xqo_pack_v_words):
             f.restype = None
             f.argtypes = [u8p, C.c_int, C.c_int, C.c_int, u32p]
+        L.xqo_merge_codes.restype = None
+        L.xqo_merge_codes.argtypes = [u8p, u8p, C.c_long, C.c_int, C.c_int, C.c_float, u8p]
         L.xqo_equivalent_bits.restype = C.c_double
         L.xqo_equivalent_bits.argtypes = [C.c_int] * 5
         L.xqo_equivalent_bits_one.restype = C.c_double
@@ -181,6 +183,16 @@ def pack_v_words(codes, B):
     return words
 
 
+def merge_codes(e0, e1, B, mode, gamma0):
+    e0 = np.ascontiguousarray(e0, np.uint8)
+    e1 = np.ascontiguousarray(e1, np.uint8)
+    out = np.zeros(e0.shape, np.uint8)
+    if e0.size:
+        lib().xqo_merge_codes(_p(e0, C.c_uint8), _p(e1, C.c_uint8), e0.size, B, mode, float(np.float32(gamma0)),
+                              _p(out, C.c_uint8))
+    return out
+
+
 # ------------------------------------------------ per-layer schedule (Alg. 1)
 @dataclass
 class Schedule:
@@ -196,6 +208,12 @@ class Schedule:
     eta2: float
     group: int
     residual: int
+    # ablation variants (Sec. 4.3): G consecutive layers share the codes of layer k of the
+    # group; merge_mode 1/2/3 forms a pair's stored codes from both layers (Appendix E)
+    share_group: int = 2
+    share_dominant: int = 0
+    merge_mode: int = 0
+    gamma0: float = 1.0
 
     def bits(self, l, is_v):
         return 2 if l < (self.vq if is_v else self.kq) else 1
@@ -203,11 +221,18 @@ class Schedule:
     def eta(self, B):
         return self.eta2 if B == 2 else self.eta1
 
-    def stores(self, l, is_v):
-        return l < (self.vm if is_v else self.km) or l % 2 == 0
-
     def code_layer(self, l, is_v):
-        return l if self.stores(l, is_v) else l - 1
+        if l < (self.vm if is_v else self.km):
+            return l
+        cl = self.share_group * (l // self.share_group) + self.share_dominant
+        return cl if cl < self.n_layers else l
+
+    def stores(self, l, is_v):
+        return self.code_layer(l, is_v) == l
+
+    def merges_next(self, l, is_v):
+        return (self.merge_mode != 0 and l + 1 < self.n_layers and self.stores(l, is_v)
+                and self.code_layer(l + 1, is_v) == l)
 
 
 def cache_slice(sch: Schedule, K, V):
@@ -227,6 +252,13 @@ def cache_slice(sch: Schedule, K, V):
         bk, bv = sch.bits(l, False), sch.bits(l, True)
         kc, ks, kz = quantize_k(K[l], g, R, bk, sch.eta(bk), sch.stores(l, False))
         vc, vs, vz = quantize_v(V[l], g, R, bv, sch.eta(bv), sch.stores(l, True))
+        # merged pair: the stored codes combine this layer's own codes with the next layer's own
+        if sch.merges_next(l, False):
+            k1 = quantize_k(K[l + 1], g, R, bk, sch.eta(bk), True)[0]
+            kc = merge_codes(kc, k1, bk, sch.merge_mode, sch.gamma0)
+        if sch.merges_next(l, True):
+            v1 = quantize_v(V[l + 1], g, R, bv, sch.eta(bv), True)[0]
+            vc = merge_codes(vc, v1, bv, sch.merge_mode, sch.gamma0)
         out.append(dict(Tq=Tq, T=T, bk=bk, bv=bv, k_codes=kc, k_scale=ks, k_zero=kz,
                         v_codes=vc, v_scale=vs, v_zero=vz,
                         k_res=K[l, Tq:].copy(), v_res=V[l, Tq:].copy()))

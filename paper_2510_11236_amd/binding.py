@@ -27,7 +27,8 @@ class XqConfig(C.Structure):
     """Mirror of struct xq_config."""
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "group",
                                          "residual", "max_tokens", "kq", "vq", "km", "vm")] + \
-               [("eta1", C.c_float), ("eta2", C.c_float)]
+               [("eta1", C.c_float), ("eta2", C.c_float), ("share_group", C.c_int32), ("share_dominant", C.c_int32),
+                ("merge_mode", C.c_int32), ("gamma0", C.c_float)]
 
 
 def lib():
@@ -170,4 +171,4 @@ def config_from_workload(w, max_tokens=None) -> XqConfig:
     """XqConfig for a synth.Workload (marshalling helper)."""
     mt = max_tokens if max_tokens is not None else w.context + w.decode_steps
     return XqConfig(w.n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.group, w.residual, mt,
-                    w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2)
+                    w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.share_group, w.share_dominant, w.merge_mode, w.gamma0)

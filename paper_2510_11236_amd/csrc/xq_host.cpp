@@ -13,9 +13,44 @@ namespace {
 inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 
 inline int bits_of(const xq_config &c, int l, bool is_v) { return l < (is_v ? c.vq : c.kq) ? 2 : 1; }
-// Appendix Alg. 1 (with the dequantization loop's conditions): a layer stores codes
-// iff it is below the sharing start or is the even layer of its pair.
-inline bool stores_codes(const xq_config &c, int l, bool is_v) { return l < (is_v ? c.vm : c.km) || (l % 2 == 0); }
+inline int group_size(const xq_config &c) { return c.share_group ? c.share_group : 2; }
+// The layer whose codes layer l reads.  Appendix Alg. 1 (with the dequantization loop's
+// conditions) for pairs: below the sharing start, or as the dominant layer of its group, a layer
+// reads its own; otherwise those of layer k of its group of G consecutive layers (Sec. 4.3
+// "Group Size": G in {2,3,4}, selection index k).  A trailing group that lacks layer k keeps
+// per-layer codes.
+inline int code_layer(const xq_config &c, int l, bool is_v) {
+    if (l < (is_v ? c.vm : c.km)) return l;
+    const int G = group_size(c);
+    const int cl = G * (l / G) + c.share_dominant;
+    return cl < c.n_layers ? cl : l;
+}
+inline bool stores_codes(const xq_config &c, int l, bool is_v) { return code_layer(c, l, is_v) == l; }
+// Stored codes of layer l are merged with those of layer l + 1 (Appendix E; pairs only).
+inline bool merges_next(const xq_config &c, int l, bool is_v) {
+    return c.merge_mode != XQ_MERGE_NONE && l + 1 < c.n_layers && stores_codes(c, l, is_v) &&
+           code_layer(c, l + 1, is_v) == l;
+}
+
+// e_m for every (e_0, e_1): entry 4*e_0 + e_1 at bits [2i, 2i+1] (2-bit codes), entry 2*e_0 + e_1
+// at bit i (1-bit codes).
+uint32_t merge_lut(const xq_config &c, int B) {
+    const int n = (1 << B) - 1;
+    uint32_t lut = 0;
+    for (int e0 = 0; e0 <= n; ++e0)
+        for (int e1 = 0; e1 <= n; ++e1) {
+            double x;
+            if (c.merge_mode == XQ_MERGE_ROUND) x = floor((double)c.gamma0 * e0 + (1.0 - (double)c.gamma0) * e1 + 0.5);
+            else if (c.merge_mode == XQ_MERGE_FLOOR) x = floor(0.5 * e0 + 0.5 * e1);
+            else if (c.merge_mode == XQ_MERGE_CEIL) x = ceil(0.5 * e0 + 0.5 * e1);
+            else x = e0;
+            int em = (int)x;
+            if (em < 0) em = 0;
+            if (em > n) em = n;
+            lut |= (uint32_t)em << (B * ((n + 1) * e0 + e1));
+        }
+    return lut;
+}
 
 int check_config(const xq_config *c) {
     if (!c) return XQ_ERR_INVALID_ARG;
@@ -32,10 +67,16 @@ int check_config(const xq_config *c) {
     int rep = c->n_q_heads / c->n_kv_heads;
     if (rep != 1 && rep != 2 && rep != 4) return XQ_ERR_UNSUPPORTED;
     if (c->head_dim == 64 && rep != 1) return XQ_ERR_UNSUPPORTED;
-    // the two layers of a sharing pair must have one bit width
-    for (int l = 1; l < c->n_layers; l += 2) {
-        if (!stores_codes(*c, l, false) && bits_of(*c, l, false) != bits_of(*c, l - 1, false)) return XQ_ERR_INVALID_ARG;
-        if (!stores_codes(*c, l, true) && bits_of(*c, l, true) != bits_of(*c, l - 1, true)) return XQ_ERR_INVALID_ARG;
+    const int G = group_size(*c);
+    if (G < 2 || G > 4) return XQ_ERR_INVALID_ARG;
+    if (c->share_dominant < 0 || c->share_dominant >= G) return XQ_ERR_INVALID_ARG;
+    if (c->merge_mode < XQ_MERGE_NONE || c->merge_mode > XQ_MERGE_CEIL) return XQ_ERR_INVALID_ARG;
+    if (c->merge_mode != XQ_MERGE_NONE && (G != 2 || c->share_dominant != 0)) return XQ_ERR_INVALID_ARG;
+    if (c->merge_mode == XQ_MERGE_ROUND && !(c->gamma0 >= 0.0f && c->gamma0 <= 1.0f)) return XQ_ERR_INVALID_ARG;
+    // the layers that share one code tensor must have one bit width
+    for (int l = 0; l < c->n_layers; ++l) {
+        if (bits_of(*c, l, false) != bits_of(*c, code_layer(*c, l, false), false)) return XQ_ERR_INVALID_ARG;
+        if (bits_of(*c, l, true) != bits_of(*c, code_layer(*c, l, true), true)) return XQ_ERR_INVALID_ARG;
     }
     return XQ_OK;
 }
@@ -65,17 +106,16 @@ Carve carve(const xq_config &c, XqLayerDesc *descs) {
         d.bv = bits_of(c, l, true);
         d.k_store = stores_codes(c, l, false);
         d.v_store = stores_codes(c, l, true);
+        d.k_merge = merges_next(c, l, false);
+        d.v_merge = merges_next(c, l, true);
+        d.k_codes = d.v_codes = 0;  // a sharing layer's are filled in below
         if (d.k_store) {
             d.k_codes = off;
             off = align256(off + nbh * (d.bk == 2 ? r.st.k_codes2 : r.st.k_codes1));
-        } else {
-            d.k_codes = descs ? descs[l - 1].k_codes : 0;
         }
         if (d.v_store) {
             d.v_codes = off;
             off = align256(off + nbh * (d.bv == 2 ? r.st.v_codes2 : r.st.v_codes1));
-        } else {
-            d.v_codes = descs ? descs[l - 1].v_codes : 0;
         }
         d.k_meta = off;
         off = align256(off + nbh * r.st.k_meta);
@@ -87,6 +127,11 @@ Carve carve(const xq_config &c, XqLayerDesc *descs) {
         off = align256(off + nbh * r.st.res);
         if (descs) descs[l] = d;
     }
+    if (descs)
+        for (int l = 0; l < c.n_layers; ++l) {
+            if (!descs[l].k_store) descs[l].k_codes = descs[code_layer(c, l, false)].k_codes;
+            if (!descs[l].v_store) descs[l].v_codes = descs[code_layer(c, l, true)].v_codes;
+        }
     r.total = off;
     return r;
 }
@@ -226,7 +271,21 @@ void xq_debug_set_tiles_per_split(xq_cache *cache, int32_t tiles_per_split) {
     if (cache) cache->tiles_per_split_override = tiles_per_split;
 }
 
+// With merging, the stored codes of a pair need both layers in one call.
+static bool merge_range_ok(const xq_config &c, int layer0, int n_layers) {
+    if (c.merge_mode == XQ_MERGE_NONE) return true;
+    for (int l = layer0; l < layer0 + n_layers; ++l)
+        for (int v = 0; v < 2; ++v) {
+            if (merges_next(c, l, v) && l + 1 >= layer0 + n_layers) return false;
+            if (l == layer0 && l > 0 && merges_next(c, l - 1, v)) return false;
+        }
+    return true;
+}
+
 static void fill_pack_consts(const xq_config &c, XqPackArgs &a) {
+    a.merge = c.merge_mode != XQ_MERGE_NONE;
+    a.lut1 = merge_lut(c, 1);
+    a.lut2 = merge_lut(c, 2);
     // eta_B * (2^B - 1) and 1 - 2 eta_B, each one fp32 operation (Eq. 12)
     volatile float e1 = c.eta1, e2 = c.eta2;
     volatile float t1 = 2.0f * e1, t2 = 2.0f * e2;
@@ -244,6 +303,7 @@ int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const vo
     for (int i = 0; i < 4; ++i)
         if (strides[i] < 0 || strides[i] % 8) return XQ_ERR_INVALID_ARG;
     if (strides[3] < c.head_dim || ((uintptr_t)k_f16 & 15) || ((uintptr_t)v_f16 & 15)) return XQ_ERR_INVALID_ARG;
+    if (!merge_range_ok(c, layer0, n_layers)) return XQ_ERR_INVALID_ARG;
     for (int l = layer0; l < layer0 + n_layers; ++l)
         if (cache->len[l] != 0) return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -300,8 +360,13 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
     if (!range_ok(cache, layer0, n_layers) || !k_new_f16 || !v_new_f16) return XQ_ERR_INVALID_ARG;
     if (((uintptr_t)k_new_f16 & 15) || ((uintptr_t)v_new_f16 & 15)) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
+    if (!merge_range_ok(c, layer0, n_layers)) return XQ_ERR_INVALID_ARG;
     for (int l = layer0; l < layer0 + n_layers; ++l)
         if (cache->len[l] >= c.max_tokens) return XQ_ERR_CAPACITY;
+    if (c.merge_mode != XQ_MERGE_NONE)  // a pair is flushed by one launch, so its layers move together
+        for (int l = layer0; l + 1 < layer0 + n_layers; ++l)
+            if ((merges_next(c, l, false) || merges_next(c, l, true)) && cache->len[l] != cache->len[l + 1])
+                return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t D = c.head_dim;
     const int64_t per_layer = (int64_t)c.batch * c.n_kv_heads * D;
@@ -382,6 +447,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         // bit 1 values shared; 0 = not fusable
         auto fuse_mode = [&](int a) -> int {
             if (!(flags & XQ_DECODE_PAIR_FUSED) || !xq_decode_can_fuse(c.head_dim, c.group, rep)) return 0;
+            if (group_size(c) != 2 || c.share_dominant != 0) return 0;
             if (a % 2 != 0 || a + 1 >= layer0 + n_layers) return 0;
             if (cache->layers[a + 1].bk != cache->layers[a].bk || cache->layers[a + 1].bv != cache->layers[a].bv) return 0;
             return (cache->layers[a + 1].k_store ? 0 : 1) | (cache->layers[a + 1].v_store ? 0 : 2);

@@ -18,6 +18,7 @@ struct XqLayerDesc {
     int64_t k_res, v_res;
     int32_t bk, bv;            // bit width of keys / values
     int32_t k_store, v_store;  // 1 if this layer writes codes
+    int32_t k_merge, v_merge;  // 1 if its stored codes are merged with those of the next layer
 };
 
 // Per (batch, kv head) strides in bytes; identical for every layer.
@@ -60,6 +61,8 @@ struct XqPackArgs {
     int32_t n_groups;   // token groups of g to quantize
     float c1_1, c2_1;   // eta1 * 1, 1 - 2 eta1     (1-bit)
     float c1_2, c2_2;   // eta2 * 3, 1 - 2 eta2     (2-bit)
+    int32_t merge;      // any layer merges codes: take the general kernel
+    uint32_t lut1, lut2;  // merged code for every (e_0, e_1), 1-bit / 2-bit
 };
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s);
 

@@ -50,6 +50,10 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
     __shared__ uint32_t tile[G * LDW];
     __shared__ float s_mn[D];  // keys: per channel; values: per (token, channel group) -- G*NJ == D
     __shared__ float s_sc[D];
+    // second layer of a pair whose stored codes are merged (Appendix E); unused otherwise
+    __shared__ uint32_t tile2[G * LDW];
+    __shared__ float s_mn2[D];
+    __shared__ float s_sc2[D];
 
     const int tid = threadIdx.x;
     const int grp = blockIdx.x;
@@ -64,6 +68,10 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
         uint32_t w = tile[t * LDW + (c >> 1)];
         return half_bits_to_float((c & 1) ? (w >> 16) : (w & 0xffffu));
     };
+    auto half2_at = [&](int t, int c) -> float {
+        uint32_t w = tile2[t * LDW + (c >> 1)];
+        return half_bits_to_float((c & 1) ? (w >> 16) : (w & 0xffffu));
+    };
 
 #pragma unroll 1
     for (int pass = 0; pass < 2; ++pass) {
@@ -73,6 +81,8 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
         const float c1 = B == 2 ? a.c1_2 : a.c1_1;
         const float c2 = B == 2 ? a.c2_2 : a.c2_1;
         const bool store = is_v ? d.v_store : d.k_store;
+        const bool mg = a.merge && (is_v ? d.v_merge : d.k_merge);  // uniform over the workgroup
+        const uint32_t lut = B == 2 ? a.lut2 : a.lut1;
         // ---- stage the tile
         const uint16_t *src;
         int64_t s_tok;
@@ -93,6 +103,25 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
             row[1] = val.y;
             row[2] = val.z;
             row[3] = val.w;
+        }
+        if (mg) {  // the same tile of the next layer
+            const uint16_t *src2;
+            if (a.from_ring) {
+                const XqLayerDesc d2 = a.layers[layer + 1];
+                src2 = (const uint16_t *)(a.arena + (is_v ? d2.v_res : d2.k_res) + (int64_t)bh * a.st.res) +
+                       (int64_t)(a.src_tok0 + grp * G) * D;
+            } else {
+                src2 = src + a.s_layer;
+            }
+            for (int idx = tid; idx < G * (D / 8); idx += 256) {
+                int t = idx / (D / 8), v = idx % (D / 8);
+                uint4 val = *(const uint4 *)(src2 + t * s_tok + v * 8);
+                uint32_t *row = &tile2[t * LDW + v * 4];
+                row[0] = val.x;
+                row[1] = val.y;
+                row[2] = val.z;
+                row[3] = val.w;
+            }
         }
         __syncthreads();
         // ---- group statistics and metadata
@@ -126,6 +155,30 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
             else
                 mp = (uint32_t *)(a.arena + d.v_meta + (int64_t)bh * a.st.v_meta) + (int64_t)dst_tok * NJ + tid;
             *mp = meta;
+            if (mg) {  // the next layer's own scale for its own codes (its metadata is written by its workgroup)
+                float mn2, mx2;
+                if (!is_v) {
+                    mn2 = mx2 = half2_at(0, tid);
+                    for (int t = 1; t < G; ++t) {
+                        float x = half2_at(t, tid);
+                        mn2 = fminf(mn2, x);
+                        mx2 = fmaxf(mx2, x);
+                    }
+                } else {
+                    int t = tid / NJ, j = tid % NJ;
+                    mn2 = mx2 = half2_at(t, j * G);
+                    for (int c = 1; c < G; ++c) {
+                        float x = half2_at(t, j * G + c);
+                        mn2 = fminf(mn2, x);
+                        mx2 = fmaxf(mx2, x);
+                    }
+                }
+                mn2 += 0.0f;
+                mx2 += 0.0f;
+                uint32_t unused;
+                s_sc2[tid] = group_params(mn2, mx2, n, c1, c2, &unused);
+                s_mn2[tid] = mn2;
+            }
         }
         __syncthreads();
         // ---- codes (skipped by a layer that takes its codes from the layer below)
@@ -142,7 +195,9 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
                     uint32_t word = 0;
                     for (int e = 0; e < per; ++e) {
                         int c = wi * per + e;
-                        word |= code_of(half_at(t, c), s_mn[c], s_sc[c], n) << (B * e);
+                        uint32_t code = code_of(half_at(t, c), s_mn[c], s_sc[c], n);
+                        if (mg) code = (lut >> (B * ((n + 1) * code + code_of(half2_at(t, c), s_mn2[c], s_sc2[c], n)))) & n;
+                        word |= code << (B * e);
                     }
                     cp[(int64_t)(dst_tok / 32 + sb) * 32 * W + ib] = word;
                 }
@@ -158,7 +213,9 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
                         int e = m * per + e2;
                         int t = sb * 32 + e / CPL, c = slot * CPL + e % CPL;
                         int gi = t * NJ + c / G;
-                        word |= code_of(half_at(t, c), s_mn[gi], s_sc[gi], n) << (B * e2);
+                        uint32_t code = code_of(half_at(t, c), s_mn[gi], s_sc[gi], n);
+                        if (mg) code = (lut >> (B * ((n + 1) * code + code_of(half2_at(t, c), s_mn2[gi], s_sc2[gi], n)))) & n;
+                        word |= code << (B * e2);
                     }
                     cp[(int64_t)(dst_tok / 32 + sb) * 64 * WS + ib] = word;
                 }
@@ -474,8 +531,10 @@ hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipSt
     if (a.n_groups <= 0) return hipSuccess;
     dim3 grid(a.n_groups, a.batch * a.n_kv_heads, n_layers), block(256);
     dim3 wgrid(2 * a.n_groups, a.batch * a.n_kv_heads, n_layers), wblock(64);
-    if (D == 128 && g == 32) xq_pack_wave_kernel<32><<<wgrid, wblock, 0, s>>>(a);
-    else if (D == 128 && g == 64) xq_pack_wave_kernel<64><<<wgrid, wblock, 0, s>>>(a);
+    if (D == 128 && g == 32 && !a.merge) xq_pack_wave_kernel<32><<<wgrid, wblock, 0, s>>>(a);
+    else if (D == 128 && g == 64 && !a.merge) xq_pack_wave_kernel<64><<<wgrid, wblock, 0, s>>>(a);
+    else if (D == 128 && g == 32) xq_pack_kernel<128, 32><<<grid, block, 0, s>>>(a);  // code merging: general kernel
+    else if (D == 128 && g == 64) xq_pack_kernel<128, 64><<<grid, block, 0, s>>>(a);
     else if (D == 64 && g == 32) xq_pack_kernel<64, 32><<<grid, block, 0, s>>>(a);
     else if (D == 64 && g == 64) xq_pack_kernel<64, 64><<<grid, block, 0, s>>>(a);
     else return hipErrorInvalidValue;

@@ -37,6 +37,10 @@ class Workload:
     outlier_scale: float = 10.0
     outlier_channels: Optional[Tuple[int, ...]] = None   # None: 4 per kv head drawn from the seed
     v_outliers: bool = False
+    share_group: int = 2    # G layers share one code tensor ...
+    share_dominant: int = 0  # ... stored by layer k of the group
+    merge_mode: int = 0     # 0 dominant only, 1 weighted round, 2 floor, 3 ceil (pairs only)
+    gamma0: float = 1.0
 
 
 def workloads():

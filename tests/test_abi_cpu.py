@@ -85,3 +85,16 @@ def test_true_bits_include_metadata(xq):
     assert xq.equivalent_bits(cfg4) == 0.75
     expect4 = ((T - r) * (0.75 + 0.5) + r * 16.0) / T
     assert abs(xq.equivalent_bits(cfg4, True, T) - expect4) < 1e-12
+
+
+def test_group_and_merge_config_checks(xq):
+    assert xq.cache_bytes(_cfg(xq, share_group=3, share_dominant=2))[0] > 0
+    assert xq.cache_bytes(_cfg(xq, merge_mode=1, gamma0=0.8))[0] > 0
+    for bad in (dict(share_group=5), dict(share_group=1), dict(share_group=3, share_dominant=3), dict(merge_mode=4),
+                dict(merge_mode=1, gamma0=1.5), dict(merge_mode=2, share_group=3), dict(merge_mode=1, share_dominant=1),
+                dict(share_group=4, kq=30, km=0)):      # group {28..31} would mix 2-bit and 1-bit layers
+        with pytest.raises(xq.XqError):
+            xq.cache_bytes(_cfg(xq, **bad))
+    # all key layers and 20 value layers stored at 2 bit -> (2 + 1.25) / 2 = 1.625 for G = 2, 3, 4
+    for G, vm in ((2, 8), (3, 14), (4, 16)):
+        assert xq.equivalent_bits(_cfg(xq, km=32, vm=vm, share_group=G)) == 1.625

@@ -222,3 +222,69 @@ def test_strided_input_and_layer_ranges(lib_):
         tl.check_stored(cache, w, st, 0, h)
         tl.check_attention(out, w, tl.oracle_attention(w, st, q, 0, h, sigma), 0, h)
     cache.close()
+
+
+@pytest.mark.parametrize("G,k,L,km,vm", [(3, 1, 7, 1, 3), (4, 3, 8, 0, 4), (3, 0, 6, 0, 0), (2, 1, 6, 2, 0)])
+def test_layer_groups(lib_, G, k, L, km, vm):
+    """Groups of G layers sharing the codes of layer k of the group (Sec. 4.3 "Group Size"),
+    including a dominant layer above its readers and a trailing group without its layer k."""
+    base = synth.workloads()[1]
+    w = synth.scaled(base, n_layers=L, batch=1, n_q_heads=2, n_kv_heads=2, kq=L, vq=L, km=km, vm=vm,
+                     eta1=1 / 6, eta2=0.045, share_group=G, share_dominant=k, seed=40 + G + k)
+    _run_prefill_case(lib_, w, 700)
+
+
+@pytest.mark.parametrize("mode,gamma0,D", [(1, 0.7, 128), (1, 0.3, 128), (1, 0.2, 64), (2, 0.5, 128), (3, 0.5, 64), (1, 1.0, 128)])
+def test_merged_pair_codes(lib_, mode, gamma0, D):
+    """Stored codes of a sharing pair formed from both layers' own codes (Appendix E): weighted
+    rounding, flooring, ceiling; prefill, then appends across two ring flushes."""
+    tl = lib_
+    base = synth.workloads()[1] if D == 128 else synth.workloads()[0]
+    w = synth.scaled(base, n_layers=4, batch=1, n_q_heads=2, n_kv_heads=2, kq=4, vq=2, km=0, vm=2, eta1=1 / 6, eta2=0.045,
+                     merge_mode=mode, gamma0=gamma0, residual=64, seed=50 + mode)
+    T0, n = 200, 70
+    K, V = synth.kv_all(w, T0 + n)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=T0 + n)
+    cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    q = synth.queries(w).cuda()
+    sigma = 1.0 / np.sqrt(D)
+    for i in range(n + 1):
+        if i in (0, 1, 40, n):
+            T = T0 + i
+            outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1)]
+            for h in range(2):
+                st = tl.oracle_slice(w, K[:, :, :, :T], V[:, :, :, :T], 0, h)
+                tl.check_stored(cache, w, st, 0, h)
+                ref = tl.oracle_attention(w, st, q, 0, h, sigma)
+                for o in outs:
+                    tl.check_attention(o, w, ref, 0, h)
+        if i < n:
+            cache.append_token(Kd[:, :, :, T0 + i].contiguous(), Vd[:, :, :, T0 + i].contiguous())
+    # the merged codes really differ from plain sharing unless gamma0 makes them the first layer's
+    plain = tl.make_cache(synth.scaled(w, merge_mode=0), max_tokens=T0 + n)
+    plain.quantize_pack(Kd, Vd)
+    same = torch.equal(plain.region(0, "k_codes"), cache.region(0, "k_codes"))
+    assert same == (mode == 1 and gamma0 == 1.0)
+    plain.close()
+    cache.close()
+
+
+def test_merge_needs_whole_pairs(lib_):
+    tl = lib_
+    from paper_2510_11236_amd import XqError
+    w = synth.scaled(synth.workloads()[0], n_layers=4, batch=1, n_q_heads=1, n_kv_heads=1, kq=4, vq=4, merge_mode=2)
+    K, V = synth.kv_all(w, 100)
+    cache = tl.make_cache(w, max_tokens=128)
+    with pytest.raises(XqError) as e:
+        cache.quantize_pack(K[:1].cuda(), V[:1].cuda(), layer0=0)
+    assert e.value.code == -1
+    with pytest.raises(XqError) as e:
+        cache.quantize_pack(K[1:3].cuda(), V[1:3].cuda(), layer0=1)
+    assert e.value.code == -1
+    cache.quantize_pack(K[:2].cuda(), V[:2].cuda(), layer0=0)
+    cache.quantize_pack(K[2:].cuda(), V[2:].cuda(), layer0=2)
+    with pytest.raises(XqError) as e:
+        cache.append_token(K[1:2, :, :, 0].contiguous().cuda(), V[1:2, :, :, 0].contiguous().cuda(), layer0=1)
+    assert e.value.code == -1
+    cache.close()

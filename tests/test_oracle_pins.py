@@ -309,6 +309,50 @@ def test_schedule_code_layer(oracle):
     assert s.bits(29, False) == 2 and s.bits(30, False) == 1 and s.bits(1, True) == 2 and s.bits(2, True) == 1
 
 
+def test_merge_rule_gamma_intervals(oracle):
+    """Appendix E: e_m = e1 + c with c fixed on each of the listed gamma0 intervals; the six
+    distinct intervals of the ablation table follow from these."""
+    from fractions import Fraction
+    for delta, c, lo, hi in _rows("gamma_intervals.txt"):
+        delta, c, lo, hi = int(delta), int(c), Fraction(lo), Fraction(hi)
+        for frac in (Fraction(1, 50), Fraction(1, 2), Fraction(49, 50)):      # points inside the open interval
+            g0 = float(lo + (hi - lo) * frac)
+            for e1 in range(0, 4 - delta):
+                e0 = e1 + delta
+                got = oracle.merge_codes(np.array([e0], np.uint8), np.array([e1], np.uint8), 2, 1, g0)[0]
+                assert got == e1 + c, (delta, c, g0, e0, e1, got)
+                # symmetric case e1 > e0: weight gamma0 still belongs to e0
+                got = oracle.merge_codes(np.array([e1], np.uint8), np.array([e0], np.uint8), 2, 1, 1.0 - g0)[0]
+                assert got == e1 + c, (delta, c, g0, got)
+    e0 = np.array([0, 1, 2, 3, 3, 0, 1, 2], np.uint8)
+    e1 = np.array([3, 2, 2, 0, 2, 1, 1, 3], np.uint8)
+    assert np.array_equal(oracle.merge_codes(e0, e1, 2, 2, 0.5), (e0.astype(int) + e1) // 2)          # flooring
+    assert np.array_equal(oracle.merge_codes(e0, e1, 2, 3, 0.5), (e0.astype(int) + e1 + 1) // 2)      # ceiling
+    assert np.array_equal(oracle.merge_codes(e0, e1, 2, 0, 0.3), e0)                                  # accelerated form
+    # gamma0 in (5/6, 1] and [0, 1/6) reduce to sharing one layer's codes (Sec. 4.3)
+    assert np.array_equal(oracle.merge_codes(e0, e1, 2, 1, 0.9), e0)
+    assert np.array_equal(oracle.merge_codes(e0, e1, 2, 1, 0.1), e1)
+
+
+def test_layer_groups_schedule(oracle):
+    """Sec. 4.3 "Group Size": all key layers and 20 value layers stored, for G = 2, 3, 4."""
+    for G, vm in ((2, 8), (3, 14), (4, 16)):
+        for k in range(G):
+            s = oracle.Schedule(32, 32, 32, 32, vm, 0.0, 0.0, 32, 128, G, k)
+            stored = [l for l in range(32) if s.stores(l, True)]
+            if G != 3:
+                assert len(stored) == 20, (G, k, len(stored))
+            for l in range(32):
+                cl = s.code_layer(l, True)
+                assert s.stores(cl, True) and (cl == l or (l >= vm and cl // G == l // G and cl % G == k))
+            assert all(s.stores(l, False) for l in range(32))
+    s = oracle.Schedule(32, 32, 32, 32, 14, 0.0, 0.0, 32, 128, 3, 0)
+    assert len([l for l in range(32) if s.stores(l, True)]) == 20
+    # trailing group without its dominant layer keeps its own codes: L = 8, G = 3, k = 2 -> layers 6, 7
+    s = oracle.Schedule(8, 8, 8, 0, 0, 0.0, 0.0, 32, 128, 3, 2)
+    assert [s.code_layer(l, False) for l in range(8)] == [2, 2, 2, 5, 5, 5, 6, 7]
+
+
 # ------------------------------------------------------------------ accounting
 def test_equivalent_bits_golden(oracle):
     for L, kq, vq, km, vm, expect, *_ in _rows("equivalent_bits.txt"):

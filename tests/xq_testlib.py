@@ -11,7 +11,8 @@ ATOL = 2e-3   # max-abs tolerance on attention outputs (fp32 accumulation), the 
 
 
 def schedule_of(w):
-    return orc.Schedule(w.n_layers, w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.group, w.residual)
+    return orc.Schedule(w.n_layers, w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.group, w.residual,
+                        w.share_group, w.share_dominant, w.merge_mode, w.gamma0)
 
 
 def np16(t):
