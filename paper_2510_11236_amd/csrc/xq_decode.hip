@@ -10,9 +10,9 @@
 // (keys: fp32 weight x fp16 code, v_fma_mix) or one dot2 per pair (values: fp16 weights)
 // accumulates in fp32.  No MFMA: one query per head makes this a bandwidth-bound GEMV.
 //
-// Work split: grid.x = packed-token splits (+1 workgroup for the fp16 ring),
-// grid.y = (sequence, kv head), grid.z = layer (or layer pair).  A workgroup has 4 waves;
-// each wave walks tiles of 128 tokens.  In a tile, a 16-lane row owns one 32-token block:
+// Work split: one workgroup per (packed-token split, sequence, kv head, layer or layer pair),
+// plus one per (sequence, kv head, layer) for the fp16 ring, in a 1-D grid.  A workgroup has
+// 4 waves; each wave walks tiles of 128 tokens.  In a tile, a 16-lane row owns one 32-token block:
 //   key phase    lane = 2 tokens x all channels; the weights q*s^ come from LDS
 //   value phase  lane = D/64 channels x all 128 tokens; the weights p*s^ come from LDS
 // Every "virtual head" v = (layer in pair) * NREP + (query head in GQA group) has its own
@@ -92,11 +92,9 @@ struct VecLoad<8> {
     }
 };
 
-// Partial result of one split for one query head: unnormalised output, running max
-// (log2 domain) and denominator.
-struct Partial {
-    static constexpr int EXTRA = 2;
-};
+// 2^x for x <= 0 (softmax weights): the bare v_exp_f32.  Results below the fp32 normal range
+// come out as 0, which is what a weight of 2^-126 may be.
+__device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // KSH / VSH: the NLAY layers of a workgroup read one key / value code tensor (a sharing pair);
 // when false each layer has its own codes and only the other tensor's unpacking is shared.
@@ -119,7 +117,6 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     constexpr int WS = CPL * BV;          // value words per slot per block
     constexpr int PERV = 32 / BV;
     constexpr int TPW = PERV / CPL;       // tokens per value word
-    constexpr int HALFV = PERV / 2;       // value codes per half
     constexpr uint32_t MASKK = ((1u << BK) - 1u) * 0x00010001u;
     constexpr uint32_t MASKV = ((1u << BV) - 1u) * 0x00010001u;
     static_assert(CPP >= 2 && CPP <= 8, "prep width");
@@ -388,7 +385,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 float tmax = wave_max(fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]));
                 float m_new = fmaxf(m_run[v], tmax);
                 if (m_new > m_run[v]) {  // wave-uniform
-                    float alpha = exp2f(m_run[v] - m_new);  // m_run = -inf gives 0
+                    float alpha = exp2_le0(m_run[v] - m_new);  // m_run = -inf gives 0
                     l_run[v] *= alpha;
 #pragma unroll
                     for (int c = 0; c < CPL; ++c) accv[v][c] *= alpha;
@@ -396,8 +393,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     for (int j = 0; j < NJ; ++j) zacc[v][j] *= alpha;
                     m_run[v] = m_new;
                 }
-                pr[0][v] = exp2f(u0 - m_new);
-                pr[1][v] = exp2f(u1 - m_new);
+                pr[0][v] = exp2_le0(u0 - m_new);
+                pr[1][v] = exp2_le0(u1 - m_new);
                 l_run[v] += pr[0][v] + pr[1][v];
             }
 #pragma unroll
@@ -527,8 +524,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     for (int c = 0; c < CR; ++c) part = fmaf(qf[v][c], kf[c], part);
                     const float u = group_sum<16>(part);
                     const float m_new = fmaxf(m_run[v], u);
-                    const float alpha = exp2f(m_run[v] - m_new);
-                    const float p = exp2f(u - m_new);
+                    const float alpha = exp2_le0(m_run[v] - m_new);
+                    const float p = exp2_le0(u - m_new);
                     l_run[v] = l_run[v] * alpha + p;
 #pragma unroll
                     for (int c = 0; c < CR; ++c) acr[v][c] = fmaf(p, vf[c], acr[v][c] * alpha);
