@@ -191,6 +191,23 @@ def main():
         by_schedule[name] = {"decode_ms": ms, "kv_tokens_per_s": w.batch * T0 / (ms * 1e-3),
                              "algorithmic_GBps": ab / (ms * 1e-3) / 1e9, "hbm_frac": ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
+    # how a real decoder must call it: one call per layer (layer l+1's query needs layer l's output)
+    def time_per_layer_calls(n=3):
+        def once():
+            for l in range(w.n_layers):
+                cache.decode_attention(qs[0][l:l + 1], sigma, out=out[l:l + 1], layer0=l)
+        once()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            once()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    per_layer_ms = time_per_layer_calls()
+
     # ---- warmup + timed steps
     def step(i, ev=None):
         cache.append_token(new_k[i], new_v[i])
@@ -230,6 +247,7 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms},
         "decode_only_by_schedule": by_schedule,
+        "decode_one_call_per_layer_ms": per_layer_ms,
         "append_ms": ms_per_step - decode_ms,
         "pack_GBps_fp16_read": pack_bytes / (pack_ms * 1e-3) / 1e9,
         "equivalent_bits": {"paper_definition": equivalent_bits(cfg), "with_metadata_and_ring": equivalent_bits(cfg, True, T0)},

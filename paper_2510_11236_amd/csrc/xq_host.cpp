@@ -145,11 +145,11 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
     return (size_t)n_layers * c.batch * c.n_q_heads * (size_t)(n_splits + 1) * (c.head_dim + 2);
 }
 
-// Split plan: whole tiles of 128 tokens per split.  Few, long workgroups are cheapest (the
-// per-workgroup prologue, cross-wave combine and partial write are paid once), so the plan
-// takes the smallest number of splits that still gives about 4096 packed-token workgroups
-// (256 CUs x 4 resident workgroups x 4 rounds), at least one tile per wave, at most
-// XQ_MAX_SPLITS, and splits of equal size.
+// Split plan: whole tiles of 128 tokens per split, equal-sized splits.  A workgroup pays a
+// fixed cost (prologue, cross-wave combine, partial write: about 3 tiles' worth) and the chip
+// holds about 1024 workgroups at once (256 CUs x 4), so the plan minimises
+//   rounds(n) * (tiles per split + 3),  rounds(n) = ceil(slices * n / 1024)
+// over the number of splits n, with at least one tile per wave and at most XQ_MAX_SPLITS.
 void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int *tiles_per_split) {
     const xq_config &c = cache->cfg;
     int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
@@ -162,13 +162,20 @@ void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int
     if (cache->tiles_per_split_override > 0) {
         tps = cache->tiles_per_split_override;
     } else {
-        int64_t slices = (int64_t)c.batch * c.n_kv_heads * n_layers;
-        int want = (int)((4096 + slices - 1) / slices);
+        const int64_t slices = (int64_t)c.batch * c.n_kv_heads * n_layers;
         int most = (tiles + 3) / 4;
-        if (want > most) want = most;
-        if (want > XQ_MAX_SPLITS) want = XQ_MAX_SPLITS;
-        if (want < 1) want = 1;
-        tps = (tiles + want - 1) / want;
+        if (most > XQ_MAX_SPLITS) most = XQ_MAX_SPLITS;
+        int64_t best_cost = -1;
+        tps = tiles;
+        for (int n = 1; n <= most; ++n) {
+            const int t = (tiles + n - 1) / n;
+            const int64_t rounds = (slices * ((tiles + t - 1) / t) + 1023) / 1024;
+            const int64_t cost = rounds * (t + 3);
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                tps = t;
+            }
+        }
     }
     int min_tps = (tiles + XQ_MAX_SPLITS - 1) / XQ_MAX_SPLITS;
     if (tps < min_tps) tps = min_tps;
