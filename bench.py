@@ -176,11 +176,14 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
+    # --schedule auto times both schedules (untimed probes) and takes the faster; an explicit
+    # schedule runs no probes, so that a profile of the run holds only warmup + timed launches
     can_fuse = any(l % 2 == 1 and (l >= w.km or l >= w.vm) for l in range(w.n_layers))
-    probe = {"sequential": time_decode(0, 10)}
-    if can_fuse:
-        probe["fused"] = time_decode(1, 10)
+    probe = {}
     if args.schedule == "auto":
+        probe["sequential"] = time_decode(0, 10)
+        if can_fuse:
+            probe["fused"] = time_decode(1, 10)
         schedule = min(probe, key=probe.get)
     else:
         schedule = args.schedule if (args.schedule != "fused" or can_fuse) else "sequential"
@@ -206,7 +209,7 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    per_layer_ms = time_per_layer_calls()
+    per_layer_ms = time_per_layer_calls() if args.schedule == "auto" else None
 
     # ---- warmup + timed steps
     def step(i, ev=None):
