@@ -58,6 +58,7 @@ int check_config(const xq_config *c) {
         c->n_q_heads < 1 || c->max_tokens < 1)
         return XQ_ERR_INVALID_ARG;
     if (c->n_q_heads % c->n_kv_heads) return XQ_ERR_INVALID_ARG;
+    if ((int64_t)c->batch * c->n_kv_heads > 65535) return XQ_ERR_UNSUPPORTED;  // one grid dimension of the pack kernels
     if (c->kq < 0 || c->vq < 0 || c->km < 0 || c->vm < 0) return XQ_ERR_INVALID_ARG;
     if (!(c->eta1 >= 0.0f && c->eta1 < 0.5f) || !(c->eta2 >= 0.0f && c->eta2 < 0.5f)) return XQ_ERR_INVALID_ARG;
     if (c->head_dim != 64 && c->head_dim != 128) return XQ_ERR_UNSUPPORTED;
