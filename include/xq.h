@@ -22,7 +22,9 @@
  *     bookkeeping in the host handle advances at call time, so calls on one
  *     handle must be issued in program order from one thread at a time.
  *   - fp16 = IEEE binary16.  Inputs must be finite.
- *   - All sequences of a batch have the same length.
+ *   - Sequences of a batch may hold different numbers of tokens (prefill them one by one
+ *     with xq_quantize_pack_seq; every append adds one token to each).  Ragged lengths need
+ *     batch <= 256 (XQ_ERR_UNSUPPORTED beyond); a uniform batch has no such limit.
  *   - Return value: 0 (XQ_OK) or a negative XQ_ERR_* code; nothing is enqueued
  *     when an error is returned, except XQ_ERR_HIP (launch failure).
  *
@@ -121,10 +123,14 @@ int xq_cache_bytes(const xq_config *cfg, size_t *arena_bytes, size_t *workspace_
 int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, xq_cache **out);
 void xq_cache_destroy(xq_cache *cache);
 
-/* Sets every layer's length to 0 (host bookkeeping only). */
+/* Sets every length to 0 (host bookkeeping only); xq_cache_reset_seq does so for one
+ * sequence in every layer, e.g. to reuse a batch slot for a new request. */
 int xq_cache_reset(xq_cache *cache);
+int xq_cache_reset_seq(xq_cache *cache, int32_t seq);
 
-/* Tokens held by a layer: total T and packed T_q (host pointers, either may be NULL). */
+/* Tokens held by a layer for one sequence: total T and packed T_q (host pointers, either may
+ * be NULL).  xq_cache_len reports sequence 0. */
+int xq_cache_len_seq(const xq_cache *cache, int32_t layer, int32_t seq, int32_t *T, int32_t *T_q);
 int xq_cache_len(const xq_cache *cache, int32_t layer, int32_t *T, int32_t *T_q);
 
 /* Prefill: quantize and pack T tokens of layers [layer0, layer0 + n_layers)
@@ -139,9 +145,15 @@ int xq_cache_len(const xq_cache *cache, int32_t layer, int32_t *T, int32_t *T_q)
 int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
                      const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream);
 
+/* The same for sequences [seq0, seq0 + n_seq) only, all with T tokens: k_f16, v_f16 hold those
+ * sequences, element (l, i, h, t, d) with i relative to seq0.  The other sequences are untouched. */
+int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int32_t seq0, int32_t n_seq,
+                         const void *k_f16, const void *v_f16, const int64_t strides[4], int32_t T,
+                         void *hip_stream);
+
 /* Decode-time append of one token per sequence to layers [layer0, layer0 + n_layers).
  * k_new_f16, v_new_f16: device fp16 [n_layers][batch][n_kv_heads][D], contiguous.
- * A layer whose ring is full first has its oldest g tokens quantized and packed (same
+ * A sequence whose ring is full first has its oldest g tokens quantized and packed (same
  * arithmetic as xq_quantize_pack, so prefill(T) + n appends == prefill(T + n) bit for bit).
  * XQ_ERR_CAPACITY when a layer already holds max_tokens. */
 int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_new_f16,
@@ -156,14 +168,15 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * when it suffices for the current lengths).  flags: 0, or XQ_DECODE_PAIR_FUSED to let one
  * workgroup serve both layers of a sharing pair so that their common codes are fetched once
  * (the result is the same up to fp32 summation order).  All layers in the range must hold
- * the same, non-zero number of tokens. */
+ * the same, non-zero number of tokens per sequence (sequences may differ from one another). */
 #define XQ_DECODE_PAIR_FUSED 1
 int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
                         void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                         int32_t flags, void *hip_stream);
 
 /* Test/debug: expands a layer's stored codes to one byte per element,
- * dev_codes_u8: device [batch][n_kv_heads][T_q][D].  XQ_ERR_STATE if the layer stores none. */
+ * dev_codes_u8: device [batch][n_kv_heads][T_q][D].  XQ_ERR_STATE if the layer stores none or
+ * its sequences differ in length. */
 int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t *dev_codes_u8,
                     void *hip_stream);
 

@@ -48,6 +48,10 @@ def lib():
         L.xq_cache_len.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.xq_cache_layout.argtypes = [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.xq_quantize_pack.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.POINTER(C.c_int64), C.c_int32, vp]
+        L.xq_quantize_pack_seq.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, C.POINTER(C.c_int64),
+                                           C.c_int32, vp]
+        L.xq_cache_len_seq.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.xq_cache_reset_seq.argtypes = [vp, C.c_int32]
         L.xq_append_token.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         L.xq_decode_attention.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, vp, C.c_size_t, C.c_int32, vp]
         L.xq_unpack_codes.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
@@ -56,7 +60,8 @@ def lib():
         L.xq_equivalent_bits.restype = C.c_double
         L.xq_equivalent_bits.argtypes = [cfgp, C.c_int32, C.c_int32]
         for name in ("xq_cache_bytes", "xq_cache_create", "xq_cache_reset", "xq_cache_len", "xq_cache_layout",
-                     "xq_quantize_pack", "xq_append_token", "xq_decode_attention", "xq_unpack_codes"):
+                     "xq_quantize_pack", "xq_append_token", "xq_decode_attention", "xq_unpack_codes",
+                     "xq_quantize_pack_seq", "xq_cache_len_seq", "xq_cache_reset_seq"):
             getattr(L, name).restype = C.c_int
         _LIB = L
     return _LIB
@@ -109,9 +114,12 @@ class XqCache:
     def reset(self):
         _check(lib().xq_cache_reset(self._h), "xq_cache_reset")
 
-    def length(self, layer=0):
+    def reset_seq(self, seq):
+        _check(lib().xq_cache_reset_seq(self._h, seq), "xq_cache_reset_seq")
+
+    def length(self, layer=0, seq=0):
         t, tq = C.c_int32(0), C.c_int32(0)
-        _check(lib().xq_cache_len(self._h, layer, C.byref(t), C.byref(tq)), "xq_cache_len")
+        _check(lib().xq_cache_len_seq(self._h, layer, seq, C.byref(t), C.byref(tq)), "xq_cache_len_seq")
         return int(t.value), int(tq.value)
 
     def layout(self, layer):
@@ -135,6 +143,15 @@ class XqCache:
         strides = (C.c_int64 * 4)(*k.stride()[:4])
         _check(lib().xq_quantize_pack(self._h, layer0, k.shape[0], C.c_void_p(k.data_ptr()),
                                       C.c_void_p(v.data_ptr()), strides, k.shape[3], _stream()), "xq_quantize_pack")
+
+    def quantize_pack_seq(self, k: torch.Tensor, v: torch.Tensor, seq0, layer0=0):
+        """k, v: fp16 [n_layers][n_seq][h_kv][T][D] for sequences seq0 .. seq0 + n_seq - 1."""
+        assert k.dtype == torch.float16 and v.dtype == torch.float16 and k.dim() == 5 and k.shape == v.shape
+        assert k.stride() == v.stride() and k.stride(4) == 1 and k.is_cuda
+        strides = (C.c_int64 * 4)(*k.stride()[:4])
+        _check(lib().xq_quantize_pack_seq(self._h, layer0, k.shape[0], seq0, k.shape[1], C.c_void_p(k.data_ptr()),
+                                          C.c_void_p(v.data_ptr()), strides, k.shape[3], _stream()),
+               "xq_quantize_pack_seq")
 
     def append_token(self, k_new: torch.Tensor, v_new: torch.Tensor, layer0=0):
         """k_new, v_new: fp16 contiguous [n_layers][b][h_kv][D]."""

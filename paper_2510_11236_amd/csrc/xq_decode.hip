@@ -154,7 +154,10 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     const int layer = a.layer0 + lz * NLAY;
     const int bi = bh / a.n_kv_heads, hkv = bh % a.n_kv_heads;
     const int row = lane >> 4, r16 = lane & 15;
-    const int n_blocks = a.Tq / 32;
+    // tokens this sequence holds (per sequence when the batch is ragged)
+    const int seqT = a.ragged ? a.seq_T[bi] : a.T;
+    const int seqTq = a.ragged ? xq_quantized_len(seqT, a.group, a.R) : a.Tq;
+    const int n_blocks = seqTq / 32;
 
     XqLayerDesc dsc[NLAY];
 #pragma unroll
@@ -201,8 +204,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
         // at large power-of-two strides, so workgroups marching in step from tile 0 would all
         // hit the same memory channels at once.  Softmax accumulation does not care about order.
         const int tile0 = split * a.tiles_per_split;
-        const int n_tiles = min(tile0 + a.tiles_per_split, (n_blocks + 3) / 4) - tile0;
-        const int rot = (int)((bh * 37u + lz * 11u) % (unsigned)n_tiles);
+        const int n_tiles = max(min(tile0 + a.tiles_per_split, (n_blocks + 3) / 4) - tile0, 0);  // 0: a shorter sequence
+        const int rot = n_tiles > 0 ? (int)((bh * 37u + lz * 11u) % (unsigned)n_tiles) : 0;
         for (int it = wave; it < n_tiles; it += 4) {
             const int tile = tile0 + (it + rot) % n_tiles;
             const int blk = tile * 4 + row;
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             float zs[NV];
             {
                 const int Gidx = tile * NGT + gi;
-                const bool g_ok = Gidx * G < a.Tq;
+                const bool g_ok = Gidx * G < seqTq;
                 uint32_t meta[NLAY][CPP];
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y) {
@@ -500,9 +503,9 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 qf[v][c] = hbits(qptr(v)[r16 * CR + c]) * a.scale_log2e;
                 acr[v][c] = 0.f;
             }
-        const int r = a.T - a.Tq;
+        const int r = seqT - seqTq;
         for (int i = wave * 4 + row; i < r; i += 16) {
-            const int slot = (a.Tq + i) % a.R;
+            const int slot = (seqTq + i) % a.R;
 #pragma unroll
             for (int y = 0; y < NLAY; ++y) {
                 const uint32_t *kp = (const uint32_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2;

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 
 #include "xq_internal.h"
@@ -220,10 +221,10 @@ int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, x
     int rc = check_config(cfg);
     if (rc) return rc;
     if (!dev_arena || !out || ((uintptr_t)dev_arena & 255)) return XQ_ERR_INVALID_ARG;
-    xq_cache *c = new (std::nothrow) xq_cache;
+    xq_cache *c = new (std::nothrow) xq_cache();
     if (!c) return XQ_ERR_INVALID_ARG;
-    memset(c, 0, sizeof(*c));
     c->cfg = *cfg;
+    c->len.assign((size_t)cfg->n_layers * cfg->batch, 0);
     Carve cv = carve(*cfg, c->layers);
     if ((size_t)cv.total > arena_bytes) {
         delete c;
@@ -243,17 +244,41 @@ int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, x
 
 void xq_cache_destroy(xq_cache *cache) { delete cache; }
 
+// lengths of layer l, one per sequence
+static inline int32_t *len_row(xq_cache *c, int l) { return c->len.data() + (size_t)l * c->cfg.batch; }
+static inline const int32_t *len_row(const xq_cache *c, int l) { return c->len.data() + (size_t)l * c->cfg.batch; }
+static bool row_uniform(const xq_cache *c, int l) {
+    const int32_t *r = len_row(c, l);
+    for (int i = 1; i < c->cfg.batch; ++i)
+        if (r[i] != r[0]) return false;
+    return true;
+}
+static bool rows_equal(const xq_cache *c, int l0, int l1) {
+    return memcmp(len_row(c, l0), len_row(c, l1), sizeof(int32_t) * c->cfg.batch) == 0;
+}
+
 int xq_cache_reset(xq_cache *cache) {
     if (!cache) return XQ_ERR_INVALID_ARG;
-    memset(cache->len, 0, sizeof(cache->len));
+    std::fill(cache->len.begin(), cache->len.end(), 0);
+    return XQ_OK;
+}
+
+int xq_cache_reset_seq(xq_cache *cache, int32_t seq) {
+    if (!cache || seq < 0 || seq >= cache->cfg.batch) return XQ_ERR_INVALID_ARG;
+    for (int l = 0; l < cache->cfg.n_layers; ++l) len_row(cache, l)[seq] = 0;
+    return XQ_OK;
+}
+
+int xq_cache_len_seq(const xq_cache *cache, int32_t layer, int32_t seq, int32_t *T, int32_t *T_q) {
+    if (!range_ok(cache, layer, 1) || seq < 0 || seq >= cache->cfg.batch) return XQ_ERR_INVALID_ARG;
+    const int t = len_row(cache, layer)[seq];
+    if (T) *T = t;
+    if (T_q) *T_q = xq_quantized_len(t, cache->cfg.group, cache->cfg.residual);
     return XQ_OK;
 }
 
 int xq_cache_len(const xq_cache *cache, int32_t layer, int32_t *T, int32_t *T_q) {
-    if (!range_ok(cache, layer, 1)) return XQ_ERR_INVALID_ARG;
-    if (T) *T = cache->len[layer];
-    if (T_q) *T_q = xq_quantized_len(cache->len[layer], cache->cfg.group, cache->cfg.residual);
-    return XQ_OK;
+    return xq_cache_len_seq(cache, layer, 0, T, T_q);
 }
 
 int xq_cache_layout(const xq_cache *cache, int32_t layer, int64_t offsets[6], int64_t sizes[6]) {
@@ -303,17 +328,20 @@ static void fill_pack_consts(const xq_config &c, XqPackArgs &a) {
     a.c2_2 = 1.0f - t2;
 }
 
-int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
-                     const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream) {
+int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int32_t seq0, int32_t n_seq,
+                         const void *k_f16, const void *v_f16, const int64_t strides[4], int32_t T,
+                         void *hip_stream) {
     if (!range_ok(cache, layer0, n_layers) || !k_f16 || !v_f16 || !strides || T < 1) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
+    if (seq0 < 0 || n_seq < 1 || seq0 + n_seq > c.batch) return XQ_ERR_INVALID_ARG;
     if (T > c.max_tokens) return XQ_ERR_CAPACITY;
     for (int i = 0; i < 4; ++i)
         if (strides[i] < 0 || strides[i] % 8) return XQ_ERR_INVALID_ARG;
     if (strides[3] < c.head_dim || ((uintptr_t)k_f16 & 15) || ((uintptr_t)v_f16 & 15)) return XQ_ERR_INVALID_ARG;
     if (!merge_range_ok(c, layer0, n_layers)) return XQ_ERR_INVALID_ARG;
     for (int l = layer0; l < layer0 + n_layers; ++l)
-        if (cache->len[l] != 0) return XQ_ERR_STATE;
+        for (int i = seq0; i < seq0 + n_seq; ++i)
+            if (len_row(cache, l)[i] != 0) return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
     const int Tq = xq_quantized_len(T, c.group, c.residual);
     if (Tq > 0) {
@@ -323,7 +351,8 @@ int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const vo
         a.layers = cache->dev_layers;
         a.st = cache->strides;
         a.layer0 = layer0;
-        a.batch = c.batch;
+        a.batch = n_seq;
+        a.bh0 = seq0 * c.n_kv_heads;
         a.n_kv_heads = c.n_kv_heads;
         a.R = c.residual;
         a.k_src = (const uint16_t *)k_f16;
@@ -345,7 +374,8 @@ int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const vo
     r.layers = cache->dev_layers;
     r.st = cache->strides;
     r.layer0 = layer0;
-    r.batch = c.batch;
+    r.batch = n_seq;
+    r.bh0 = seq0 * c.n_kv_heads;
     r.n_kv_heads = c.n_kv_heads;
     r.R = c.residual;
     r.D = c.head_dim;
@@ -359,8 +389,15 @@ int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const vo
     r.dst_tok0 = Tq;
     r.n_tok = T - Tq;
     if (xq_launch_ring_write(r, n_layers, s) != hipSuccess) return XQ_ERR_HIP;
-    for (int l = layer0; l < layer0 + n_layers; ++l) cache->len[l] = T;
+    for (int l = layer0; l < layer0 + n_layers; ++l)
+        for (int i = seq0; i < seq0 + n_seq; ++i) len_row(cache, l)[i] = T;
     return XQ_OK;
+}
+
+int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
+                     const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream) {
+    if (!cache) return XQ_ERR_INVALID_ARG;
+    return xq_quantize_pack_seq(cache, layer0, n_layers, 0, cache->cfg.batch, k_f16, v_f16, strides, T, hip_stream);
 }
 
 int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_new_f16,
@@ -369,23 +406,30 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
     if (((uintptr_t)k_new_f16 & 15) || ((uintptr_t)v_new_f16 & 15)) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
     if (!merge_range_ok(c, layer0, n_layers)) return XQ_ERR_INVALID_ARG;
-    for (int l = layer0; l < layer0 + n_layers; ++l)
-        if (cache->len[l] >= c.max_tokens) return XQ_ERR_CAPACITY;
+    for (int l = layer0; l < layer0 + n_layers; ++l) {
+        for (int i = 0; i < c.batch; ++i)
+            if (len_row(cache, l)[i] >= c.max_tokens) return XQ_ERR_CAPACITY;
+        if (!row_uniform(cache, l) && c.batch > XQ_MAX_RAGGED) return XQ_ERR_UNSUPPORTED;
+    }
     if (c.merge_mode != XQ_MERGE_NONE)  // a pair is flushed by one launch, so its layers move together
         for (int l = layer0; l + 1 < layer0 + n_layers; ++l)
-            if ((merges_next(c, l, false) || merges_next(c, l, true)) && cache->len[l] != cache->len[l + 1])
+            if ((merges_next(c, l, false) || merges_next(c, l, true)) && !rows_equal(cache, l, l + 1))
                 return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t D = c.head_dim;
     const int64_t per_layer = (int64_t)c.batch * c.n_kv_heads * D;
-    // runs of consecutive layers with one length share their launches
+    // runs of consecutive layers with the same lengths share their launches
     int l = layer0;
     while (l < layer0 + n_layers) {
         int e = l + 1;
-        while (e < layer0 + n_layers && cache->len[e] == cache->len[l]) ++e;
-        const int T = cache->len[l];
-        const int Tq = xq_quantized_len(T, c.group, c.residual);
-        if (T - Tq == c.residual) {  // ring full: its oldest g tokens become a packed group
+        while (e < layer0 + n_layers && rows_equal(cache, e, l)) ++e;
+        const int32_t *row = len_row(cache, l);
+        const bool ragged = !row_uniform(cache, l);
+        bool any_flush = false;  // a full ring: its oldest g tokens become a packed group
+        for (int i = 0; i < c.batch; ++i)
+            any_flush |= row[i] - xq_quantized_len(row[i], c.group, c.residual) == c.residual;
+        if (any_flush) {
+            const int Tq = xq_quantized_len(row[0], c.group, c.residual);
             XqPackArgs a;
             memset(&a, 0, sizeof(a));
             a.arena = cache->arena;
@@ -399,6 +443,8 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
             a.src_tok0 = Tq % c.residual;
             a.dst_tok0 = Tq;
             a.n_groups = 1;
+            a.ragged = ragged;
+            if (ragged) memcpy(a.seq_T, row, sizeof(int32_t) * c.batch);
             fill_pack_consts(c, a);
             if (xq_launch_pack(a, c.head_dim, c.group, e - l, s) != hipSuccess) return XQ_ERR_HIP;
         }
@@ -419,10 +465,13 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
         r.s_head = D;
         r.s_tok = D;
         r.src_tok0 = 0;
-        r.dst_tok0 = T;
+        r.dst_tok0 = row[0];
         r.n_tok = 1;
+        r.ragged = ragged;
+        if (ragged) memcpy(r.seq_T, row, sizeof(int32_t) * c.batch);
         if (xq_launch_ring_write(r, e - l, s) != hipSuccess) return XQ_ERR_HIP;
-        for (int k = l; k < e; ++k) cache->len[k] = T + 1;
+        for (int k = l; k < e; ++k)
+            for (int i = 0; i < c.batch; ++i) len_row(cache, k)[i] += 1;
         l = e;
     }
     return XQ_OK;
@@ -435,10 +484,16 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
     if (flags & ~XQ_DECODE_PAIR_FUSED) return XQ_ERR_INVALID_ARG;
     if (((uintptr_t)q_f16 & 3) || ((uintptr_t)out_f32 & 3) || ((uintptr_t)dev_workspace & 15)) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
-    const int T = cache->len[layer0];
-    if (T < 1) return XQ_ERR_STATE;
+    const int32_t *row = len_row(cache, layer0);
+    int T = 0;  // the longest sequence plans the splits
+    for (int i = 0; i < c.batch; ++i) {
+        if (row[i] < 1) return XQ_ERR_STATE;
+        if (row[i] > T) T = row[i];
+    }
     for (int l = layer0; l < layer0 + n_layers; ++l)
-        if (cache->len[l] != T) return XQ_ERR_STATE;
+        if (!rows_equal(cache, l, layer0)) return XQ_ERR_STATE;
+    const bool ragged = !row_uniform(cache, layer0);
+    if (ragged && c.batch > XQ_MAX_RAGGED) return XQ_ERR_UNSUPPORTED;
     const int Tq = xq_quantized_len(T, c.group, c.residual);
     int n_splits, tps;
     plan_splits(cache, Tq, n_layers, &n_splits, &tps);
@@ -483,8 +538,11 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.n_q_heads = c.n_q_heads;
         a.n_kv_heads = c.n_kv_heads;
         a.R = c.residual;
+        a.group = c.group;
         a.T = T;
         a.Tq = Tq;
+        a.ragged = ragged;
+        if (ragged) memcpy(a.seq_T, row, sizeof(int32_t) * c.batch);
         a.n_splits = n_splits;
         a.tiles_per_split = tps;
         a.q = (const uint16_t *)q_f16 + (int64_t)(l - layer0) * per_layer_q;
@@ -503,7 +561,8 @@ int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t 
     const xq_config &c = cache->cfg;
     const XqLayerDesc &d = cache->layers[layer];
     if (!(is_v ? d.v_store : d.k_store)) return XQ_ERR_STATE;
-    const int Tq = xq_quantized_len(cache->len[layer], c.group, c.residual);
+    if (!row_uniform(cache, layer)) return XQ_ERR_STATE;  // the dense output needs one length
+    const int Tq = xq_quantized_len(len_row(cache, layer)[0], c.group, c.residual);
     if (Tq == 0) return XQ_ERR_STATE;
     XqUnpackArgs a;
     a.B = is_v ? d.bv : d.bk;

@@ -3,11 +3,14 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "xq.h"
 
 #define XQ_MAX_LAYERS 256
 #define XQ_MAX_SPLITS 64     // packed-token splits per (layer, sequence, kv head)
 #define XQ_TILE_TOKENS 128   // tokens one wave handles per iteration of the decode loop
+#define XQ_MAX_RAGGED 256    // largest batch whose sequences may have different lengths
 
 // Where a layer's regions live inside the arena (byte offsets) and what it holds.
 // k_codes / v_codes point at the codes the layer READS: its own, or those of the
@@ -35,11 +38,11 @@ struct xq_cache {
     XqLayerDesc layers[XQ_MAX_LAYERS];
     XqLayerDesc *dev_layers;  // copy at the start of the arena
     XqStrides strides;
-    int32_t len[XQ_MAX_LAYERS];
+    std::vector<int32_t> len;  // tokens held, [layer][sequence]
     int32_t tiles_per_split_override;  // 0 = automatic
 };
 
-static inline int xq_quantized_len(int T, int g, int R) {
+__host__ __device__ static inline int xq_quantized_len(int T, int g, int R) {
     int over = T - R;
     return over <= 0 ? 0 : g * ((over + g - 1) / g);
 }
@@ -63,6 +66,11 @@ struct XqPackArgs {
     float c1_2, c2_2;   // eta2 * 3, 1 - 2 eta2     (2-bit)
     int32_t merge;      // any layer merges codes: take the general kernel
     uint32_t lut1, lut2;  // merged code for every (e_0, e_1), 1-bit / 2-bit
+    int32_t bh0;        // first (sequence, kv head) slice served; grid.y counts from it
+    // ring flush of a batch with per-sequence lengths: sequence i holds seq_T[i] tokens and is
+    // flushed (its oldest g ring tokens) only if its ring is full; src/dst offsets follow from it
+    int32_t ragged;
+    int32_t seq_T[XQ_MAX_RAGGED];
 };
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s);
 
@@ -76,6 +84,9 @@ struct XqRingArgs {
     int32_t src_tok0;  // first source token
     int32_t dst_tok0;  // absolute index of the first token written (slot = index mod R)
     int32_t n_tok;
+    int32_t bh0;       // first (sequence, kv head) slice served
+    int32_t ragged;    // per-sequence destination index seq_T[i] instead of dst_tok0
+    int32_t seq_T[XQ_MAX_RAGGED];
 };
 hipError_t xq_launch_ring_write(const XqRingArgs &a, int n_layers, hipStream_t s);
 
@@ -92,6 +103,9 @@ struct XqDecodeArgs {
     float *ws;          // partials: [n_layers][b][h_q][n_splits + 1][D + 2]
     float scale_log2e;  // sm_scale * log2(e)
     int32_t n_launch_z;  // layers (or layer pairs) in this launch; set by the launcher
+    int32_t ragged;      // per-sequence lengths seq_T[i] instead of T (Tq follows from the split rule)
+    int32_t group;       // g, for the split rule
+    int32_t seq_T[XQ_MAX_RAGGED];
 };
 // bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs
 hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv, int n_rep,

@@ -57,12 +57,20 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
 
     const int tid = threadIdx.x;
     const int grp = blockIdx.x;
-    const int bh = blockIdx.y;
+    const int bh = a.bh0 + blockIdx.y;
     const int lz = blockIdx.z;
     const int layer = a.layer0 + lz;
     const XqLayerDesc d = a.layers[layer];
-    const int bi = bh / a.n_kv_heads, hh = bh % a.n_kv_heads;
-    const int dst_tok = a.dst_tok0 + grp * G;
+    const int bi = blockIdx.y / a.n_kv_heads, hh = blockIdx.y % a.n_kv_heads;  // source indices are local to the call
+    int src_tok0 = a.src_tok0, dst_tok0 = a.dst_tok0;
+    if (a.ragged) {  // per-sequence ring flush: only sequences whose ring is full take part
+        const int T = a.seq_T[bh / a.n_kv_heads];
+        const int Tq = xq_quantized_len(T, G, a.R);
+        if (T - Tq != a.R) return;
+        src_tok0 = Tq % a.R;
+        dst_tok0 = Tq;
+    }
+    const int dst_tok = dst_tok0 + grp * G;
 
     auto half_at = [&](int t, int c) -> float {
         uint32_t w = tile[t * LDW + (c >> 1)];
@@ -88,11 +96,11 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
         int64_t s_tok;
         if (a.from_ring) {
             src = (const uint16_t *)(a.arena + (is_v ? d.v_res : d.k_res) + (int64_t)bh * a.st.res) +
-                  (int64_t)(a.src_tok0 + grp * G) * D;
+                  (int64_t)(src_tok0 + grp * G) * D;
             s_tok = D;
         } else {
             src = (is_v ? a.v_src : a.k_src) + lz * a.s_layer + bi * a.s_batch + hh * a.s_head +
-                  (int64_t)(a.src_tok0 + grp * G) * a.s_tok;
+                  (int64_t)(src_tok0 + grp * G) * a.s_tok;
             s_tok = a.s_tok;
         }
         for (int idx = tid; idx < G * (D / 8); idx += 256) {
@@ -109,7 +117,7 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
             if (a.from_ring) {
                 const XqLayerDesc d2 = a.layers[layer + 1];
                 src2 = (const uint16_t *)(a.arena + (is_v ? d2.v_res : d2.k_res) + (int64_t)bh * a.st.res) +
-                       (int64_t)(a.src_tok0 + grp * G) * D;
+                       (int64_t)(src_tok0 + grp * G) * D;
             } else {
                 src2 = src + a.s_layer;
             }
@@ -455,19 +463,27 @@ __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
     const int lane = threadIdx.x;
     const bool is_v = (int)blockIdx.x >= a.n_groups;
     const int grp = is_v ? blockIdx.x - a.n_groups : blockIdx.x;
-    const int bh = blockIdx.y, lz = blockIdx.z;
+    const int bh = a.bh0 + blockIdx.y, lz = blockIdx.z;
     const XqLayerDesc d = a.layers[a.layer0 + lz];
-    const int bi = bh / a.n_kv_heads, hh = bh % a.n_kv_heads;
-    const int dst_tok = a.dst_tok0 + grp * G;
+    const int bi = blockIdx.y / a.n_kv_heads, hh = blockIdx.y % a.n_kv_heads;  // source indices are local to the call
+    int src_tok0 = a.src_tok0, dst_tok0 = a.dst_tok0;
+    if (a.ragged) {  // per-sequence ring flush: only sequences whose ring is full take part
+        const int T = a.seq_T[bh / a.n_kv_heads];
+        const int Tq = xq_quantized_len(T, G, a.R);
+        if (T - Tq != a.R) return;
+        src_tok0 = Tq % a.R;
+        dst_tok0 = Tq;
+    }
+    const int dst_tok = dst_tok0 + grp * G;
     const uint16_t *src;
     int64_t s_tok;
     if (a.from_ring) {
         src = (const uint16_t *)(a.arena + (is_v ? d.v_res : d.k_res) + (int64_t)bh * a.st.res) +
-              (int64_t)(a.src_tok0 + grp * G) * D;
+              (int64_t)(src_tok0 + grp * G) * D;
         s_tok = D;
     } else {
         src = (is_v ? a.v_src : a.k_src) + lz * a.s_layer + bi * a.s_batch + hh * a.s_head +
-              (int64_t)(a.src_tok0 + grp * G) * a.s_tok;
+              (int64_t)(src_tok0 + grp * G) * a.s_tok;
         s_tok = a.s_tok;
     }
     uint32_t rows[G];
@@ -484,15 +500,16 @@ __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
 
 // Copies n_tok tokens into the fp16 rings (token index t -> slot t mod R), keys and values.
 __global__ __launch_bounds__(256) void xq_ring_write_kernel(XqRingArgs a) {
-    const int bh = blockIdx.y, lz = blockIdx.z;
+    const int bh = a.bh0 + blockIdx.y, lz = blockIdx.z;
     const XqLayerDesc d = a.layers[a.layer0 + lz];
-    const int bi = bh / a.n_kv_heads, hh = bh % a.n_kv_heads;
+    const int bi = blockIdx.y / a.n_kv_heads, hh = blockIdx.y % a.n_kv_heads;  // source indices are local to the call
+    const int dst_tok0 = a.ragged ? a.seq_T[bh / a.n_kv_heads] : a.dst_tok0;
     const int vec = a.D / 8;
     const int total = a.n_tok * vec;
     for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
         int t = idx / vec, v = idx % vec;
         int64_t so = lz * a.s_layer + bi * a.s_batch + hh * a.s_head + (int64_t)(a.src_tok0 + t) * a.s_tok + v * 8;
-        int slot = (a.dst_tok0 + t) % a.R;
+        int slot = (dst_tok0 + t) % a.R;
         int64_t doff = (int64_t)bh * a.st.res + ((int64_t)slot * a.D + v * 8) * 2;
         *(uint4 *)(a.arena + d.k_res + doff) = *(const uint4 *)(a.k_src + so);
         *(uint4 *)(a.arena + d.v_res + doff) = *(const uint4 *)(a.v_src + so);

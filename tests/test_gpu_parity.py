@@ -288,3 +288,79 @@ def test_merge_needs_whole_pairs(lib_):
         cache.append_token(K[1:2, :, :, 0].contiguous().cuda(), V[1:2, :, :, 0].contiguous().cuda(), layer0=1)
     assert e.value.code == -1
     cache.close()
+
+
+@pytest.mark.parametrize("rep,g,vq", [(1, 32, 4), (4, 64, 0)])
+def test_ragged_batch(lib_, rep, g, vq):
+    """Sequences of one batch with different lengths: prefilled one by one (one still empty of
+    packed tokens, one exactly at the ring size), then appended together so that their rings
+    flush at different steps; every slice is checked against the oracle on its own history."""
+    tl = lib_
+    base = synth.workloads()[1]
+    lens = [40, 128, 129, 1000, 417]
+    w = synth.scaled(base, n_layers=4, batch=len(lens), n_q_heads=2 * rep, n_kv_heads=2, group=g, residual=128,
+                     kq=4, vq=vq, km=0, vm=0, eta1=1 / 6, eta2=0.045, seed=60 + rep)
+    n = 70
+    K, V = synth.kv_all(w, max(lens) + n)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=max(lens) + n)
+    for i, T in enumerate(lens):
+        cache.quantize_pack_seq(Kd[:, i:i + 1, :, :T], Vd[:, i:i + 1, :, :T], seq0=i)
+    sigma = 1.0 / np.sqrt(128)
+    q = synth.queries(w).cuda()
+
+    def check(step):
+        outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1)]
+        for bi, T in enumerate(lens):
+            T = T + step
+            assert cache.length(0, bi)[0] == T
+            h = bi % 2
+            st = tl.oracle_slice(w, K[:, :, :, :T], V[:, :, :, :T], bi, h)
+            _check_stored_seq(tl, cache, w, st, bi, h)
+            ref = tl.oracle_attention(w, st, q, bi, h, sigma)
+            for o in outs:
+                tl.check_attention(o, w, ref, bi, h)
+
+    check(0)
+    for s in range(1, n + 1):
+        # sequence i's next token is its own token index lens[i] + s - 1
+        kn = torch.stack([Kd[:, i, :, lens[i] + s - 1] for i in range(len(lens))], 1).contiguous()
+        vn = torch.stack([Vd[:, i, :, lens[i] + s - 1] for i in range(len(lens))], 1).contiguous()
+        cache.append_token(kn, vn)
+        if s in (1, 2, 23, 24, 56, n):
+            check(s)
+    # a finished request frees its slot: reset one sequence and prefill a new, shorter one
+    cache.reset_seq(3)
+    cache.quantize_pack_seq(Kd[:, 0:1, :, :200], Vd[:, 0:1, :, :200], seq0=3)
+    out = cache.decode_attention(q, sigma)
+    st = tl.oracle_slice(w, K[:, :, :, :200], V[:, :, :, :200], 0, 1)
+    ref = tl.oracle_attention(w, st, q[:, 3:4].expand(-1, 1, -1, -1).contiguous(), 0, 1, sigma)
+    got = out[:, 3, rep:2 * rep].cpu().numpy()
+    for l in range(w.n_layers):
+        assert np.max(np.abs(got[l] - ref[l])) <= tl.ATOL
+    cache.close()
+
+
+def _check_stored_seq(tl, cache, w, state, bi, h):
+    """check_stored for a ragged batch (lengths are per sequence)."""
+    from oracle import xq_oracle as orc
+    cfg = cache.cfg
+    D, g, R = cfg.head_dim, cfg.group, cfg.residual
+    bh = bi * cfg.n_kv_heads + h
+    sch = tl.schedule_of(w)
+    for l in range(cfg.n_layers):
+        st = state[l]
+        T, Tq = cache.length(l, bi)
+        assert (T, Tq) == (st["T"], st["Tq"]), (l, bi, T, Tq, st["T"], st["Tq"])
+        for is_v, pre in ((False, "k"), (True, "v")):
+            B = st["b" + pre]
+            meta = cache.region(l, pre + "_meta")[bh].cpu().numpy().view(np.uint32)
+            exp_meta = st[pre + "_scale"].astype(np.uint32).reshape(-1) | (st[pre + "_zero"].astype(np.uint32).reshape(-1) << 16)
+            assert np.array_equal(meta[:exp_meta.size], exp_meta), (l, bi, pre, "meta")
+            if sch.stores(l, is_v):
+                words = cache.region(l, pre + "_codes")[bh].cpu().numpy().view(np.uint32)[:Tq * D * B // 32]
+                exp = (orc.pack_v_words if is_v else orc.pack_k_words)(st[pre + "_codes"], B)
+                assert np.array_equal(words, exp), (l, bi, pre, "codes")
+            ring = cache.region(l, pre + "_res")[bh].cpu().numpy().view(np.uint16).reshape(R, D)
+            for i in range(T - Tq):
+                assert np.array_equal(ring[(Tq + i) % R], st[pre + "_res"][i]), (l, bi, pre, "ring", i)
