@@ -180,6 +180,14 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
 int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t *dev_codes_u8,
                     void *hip_stream);
 
+/* Diagnostic of Sec. 3.3.2 (the analysis that motivates sharing): histogram of the absolute
+ * differences |c_l - c_{l+1}| between the stored codes of two adjacent layers at the same
+ * positions, over all packed tokens of all sequences.  Both layers must store their own codes
+ * with one bit width and hold equal lengths (XQ_ERR_STATE otherwise).  dev_counts_u64: device,
+ * 4 values (differences 0..3; 1-bit codes use the first two); overwritten. */
+int xq_code_delta_histogram(const xq_cache *cache, int32_t layer, int32_t is_v, uint64_t *dev_counts_u64,
+                            void *hip_stream);
+
 /* Byte offsets of a layer's regions inside the arena (host pointer to 6 values:
  * k_codes, v_codes, k_meta, v_meta, k_residual, v_residual; a code offset is -1 for a layer
  * that stores none) and, in sizes[6], the bytes of each region per (batch, kv head). */

@@ -55,6 +55,8 @@ def lib():
         L.xq_append_token.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         L.xq_decode_attention.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, vp, C.c_size_t, C.c_int32, vp]
         L.xq_unpack_codes.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
+        L.xq_code_delta_histogram.restype = C.c_int
+        L.xq_code_delta_histogram.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
         L.xq_debug_set_tiles_per_split.restype = None
         L.xq_debug_set_tiles_per_split.argtypes = [vp, C.c_int32]
         L.xq_equivalent_bits.restype = C.c_double
@@ -178,6 +180,13 @@ class XqCache:
         out = torch.empty((c.batch, c.n_kv_heads, tq, c.head_dim), dtype=torch.uint8, device=self.device)
         _check(lib().xq_unpack_codes(self._h, layer, int(is_v), C.c_void_p(out.data_ptr()), _stream()),
                "xq_unpack_codes")
+        return out
+
+    def code_delta_histogram(self, layer, is_v):
+        """Counts of |c_layer - c_layer+1| = 0..3 over all packed elements (int64 tensor of 4)."""
+        out = torch.empty(4, dtype=torch.int64, device=self.device)
+        _check(lib().xq_code_delta_histogram(self._h, layer, int(is_v), C.c_void_p(out.data_ptr()), _stream()),
+               "xq_code_delta_histogram")
         return out
 
     def set_tiles_per_split(self, n):

@@ -577,6 +577,34 @@ int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t 
     return xq_launch_unpack(a, (hipStream_t)hip_stream) == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
+int xq_code_delta_histogram(const xq_cache *cache, int32_t layer, int32_t is_v, uint64_t *dev_counts_u64,
+                            void *hip_stream) {
+    if (!range_ok(cache, layer, 2) || !dev_counts_u64 || ((uintptr_t)dev_counts_u64 & 7)) return XQ_ERR_INVALID_ARG;
+    const xq_config &c = cache->cfg;
+    const XqLayerDesc &d0 = cache->layers[layer], &d1 = cache->layers[layer + 1];
+    if (!(is_v ? d0.v_store && d1.v_store : d0.k_store && d1.k_store)) return XQ_ERR_STATE;
+    const int B = is_v ? d0.bv : d0.bk;
+    if (B != (is_v ? d1.bv : d1.bk) || !rows_equal(cache, layer, layer + 1)) return XQ_ERR_STATE;
+    const bool ragged = !row_uniform(cache, layer);
+    if (ragged && c.batch > XQ_MAX_RAGGED) return XQ_ERR_UNSUPPORTED;
+    XqDeltaArgs a;
+    memset(&a, 0, sizeof(a));
+    a.codes_a = cache->arena + (is_v ? d0.v_codes : d0.k_codes);
+    a.codes_b = cache->arena + (is_v ? d1.v_codes : d1.k_codes);
+    a.stride = is_v ? (B == 2 ? cache->strides.v_codes2 : cache->strides.v_codes1)
+                    : (B == 2 ? cache->strides.k_codes2 : cache->strides.k_codes1);
+    a.n_kv_heads = c.n_kv_heads;
+    a.n_bh = c.batch * c.n_kv_heads;
+    a.B = B;
+    a.words_per_token = c.head_dim * B / 32;
+    a.ragged = ragged;
+    a.Tq = xq_quantized_len(len_row(cache, layer)[0], c.group, c.residual);
+    if (ragged)
+        for (int i = 0; i < c.batch; ++i) a.seq_Tq[i] = xq_quantized_len(len_row(cache, layer)[i], c.group, c.residual);
+    a.counts = (unsigned long long *)dev_counts_u64;
+    return xq_launch_delta_histogram(a, (hipStream_t)hip_stream) == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
 double xq_equivalent_bits(const xq_config *cfg, int32_t include_metadata, int32_t T) {
     if (check_config(cfg)) return -1.0;
     const xq_config &c = *cfg;

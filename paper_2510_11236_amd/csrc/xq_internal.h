@@ -120,3 +120,14 @@ struct XqUnpackArgs {
     uint8_t *out;
 };
 hipError_t xq_launch_unpack(const XqUnpackArgs &a, hipStream_t s);
+
+struct XqDeltaArgs {
+    const char *codes_a, *codes_b;  // code regions of the two layers
+    int64_t stride;                 // per (batch, kv head), bytes
+    int32_t n_kv_heads, n_bh, B;
+    int32_t words_per_token;        // D * B / 32
+    int32_t ragged, Tq;             // packed tokens, or per sequence from seq_Tq
+    int32_t seq_Tq[XQ_MAX_RAGGED];
+    unsigned long long *counts;     // 4 values
+};
+hipError_t xq_launch_delta_histogram(const XqDeltaArgs &a, hipStream_t s);

@@ -542,7 +542,49 @@ __global__ __launch_bounds__(256) void xq_unpack_kernel(XqUnpackArgs a) {
     }
 }
 
+__global__ void xq_zero_counts_kernel(unsigned long long *c) { c[threadIdx.x] = 0ull; }
+
+// Histogram of |code_a - code_b| over the packed words of two layers (same layout on both
+// sides, so corresponding fields are corresponding elements).  grid.y = (sequence, kv head).
+__global__ __launch_bounds__(256) void xq_delta_histogram_kernel(XqDeltaArgs a) {
+    __shared__ unsigned long long s_cnt[4];
+    if (threadIdx.x < 4) s_cnt[threadIdx.x] = 0ull;
+    __syncthreads();
+    const int bh = blockIdx.y;
+    const int Tq = a.ragged ? a.seq_Tq[bh / a.n_kv_heads] : a.Tq;
+    const int64_t n_words = (int64_t)Tq * a.words_per_token;
+    const uint32_t *wa = (const uint32_t *)(a.codes_a + (int64_t)bh * a.stride);
+    const uint32_t *wb = (const uint32_t *)(a.codes_b + (int64_t)bh * a.stride);
+    unsigned int cnt[4] = {0, 0, 0, 0};
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * 256) {
+        const uint32_t x = wa[i], y = wb[i];
+        if (a.B == 1) {
+            const int d1 = __builtin_popcount(x ^ y);
+            cnt[1] += d1;
+            cnt[0] += 32 - d1;
+        } else {
+#pragma unroll
+            for (int f = 0; f < 16; ++f) {
+                const int d = (int)((x >> (2 * f)) & 3u) - (int)((y >> (2 * f)) & 3u);
+                cnt[d < 0 ? -d : d] += 1;
+            }
+        }
+    }
+    for (int k = 0; k < 4; ++k)
+        if (cnt[k]) atomicAdd(&s_cnt[k], (unsigned long long)cnt[k]);
+    __syncthreads();
+    if (threadIdx.x < 4 && s_cnt[threadIdx.x]) atomicAdd(&a.counts[threadIdx.x], s_cnt[threadIdx.x]);
+}
+
 }  // namespace
+
+hipError_t xq_launch_delta_histogram(const XqDeltaArgs &a, hipStream_t s) {
+    xq_zero_counts_kernel<<<dim3(1), dim3(4), 0, s>>>(a.counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    xq_delta_histogram_kernel<<<dim3(64, a.n_bh), dim3(256), 0, s>>>(a);
+    return hipGetLastError();
+}
 
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s) {
     if (a.n_groups <= 0) return hipSuccess;

@@ -364,3 +364,77 @@ def _check_stored_seq(tl, cache, w, state, bi, h):
             ring = cache.region(l, pre + "_res")[bh].cpu().numpy().view(np.uint16).reshape(R, D)
             for i in range(T - Tq):
                 assert np.array_equal(ring[(Tq + i) % R], st[pre + "_res"][i]), (l, bi, pre, "ring", i)
+
+
+def test_determinism_and_error_codes(lib_):
+    """Same inputs twice give identical bits (no atomics, no arrival-order dependence in the
+    split merge), also across a pack of the same data into a second cache; plus the decode
+    entry point's error paths."""
+    tl = lib_
+    from paper_2510_11236_amd import XqError
+    w = synth.scaled(synth.workloads()[1], n_layers=4, batch=2, n_q_heads=4, n_kv_heads=4, km=0, vm=0,
+                     eta1=1 / 6, eta2=0.045)
+    T = 3000
+    K, V = synth.kv_all(w, T)
+    Kd, Vd = K.cuda(), V.cuda()
+    c1, c2 = tl.make_cache(w, max_tokens=T + 1), tl.make_cache(w, max_tokens=T + 1)
+    c1.quantize_pack(Kd, Vd)
+    c2.quantize_pack(Kd, Vd)
+    for name in ("k_codes", "v_codes", "k_meta", "v_meta", "k_res", "v_res"):
+        for l in range(4):
+            a, b = c1.region(l, name), c2.region(l, name)
+            if a is not None:
+                n = {"k_codes": 2944 * 32, "v_codes": 2944 * 32, "k_meta": 2944 // 32 * 512, "v_meta": 2944 * 16,
+                     "k_res": 56 * 256, "v_res": 56 * 256}[name]   # T_q = 2944, r = 56 tokens used
+                assert torch.equal(a[:, :n], b[:, :n]), (name, l)
+    q = synth.queries(w).cuda()
+    for flags in (0, 1):
+        o1 = c1.decode_attention(q, 0.1, flags=flags)
+        o2 = c1.decode_attention(q, 0.1, flags=flags)
+        o3 = c2.decode_attention(q, 0.1, flags=flags)
+        assert torch.equal(o1, o2) and torch.equal(o1, o3)
+    # error paths of decode: bad flag, layers of different length, workspace too small
+    with pytest.raises(XqError) as e:
+        c1.decode_attention(q, 0.1, flags=2)
+    assert e.value.code == -1
+    c1.append_token(Kd[:2, :, :, 0].contiguous(), Vd[:2, :, :, 0].contiguous(), layer0=0)
+    with pytest.raises(XqError) as e:
+        c1.decode_attention(q, 0.1)
+    assert e.value.code == -4
+    small = c2.workspace
+    c2.workspace = small[:1024]
+    with pytest.raises(XqError) as e:
+        c2.decode_attention(q, 0.1)
+    assert e.value.code == -3
+    c2.workspace = small
+    c1.close()
+    c2.close()
+
+
+def test_code_delta_histogram(lib_):
+    """Sec. 3.3.2 diagnostic: adjacent-layer code differences counted on the device equal the
+    counts from the oracle's codes; on the correlated synthetic layers most differences are 0/1."""
+    tl = lib_
+    from paper_2510_11236_amd import XqError
+    w = synth.scaled(synth.workloads()[1], n_layers=4, batch=2, n_q_heads=2, n_kv_heads=2, kq=4, vq=2, km=4, vm=4,
+                     eta1=0.0, eta2=0.0)
+    T = 1000
+    K, V = synth.kv_all(w, T)
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(K.cuda(), V.cuda())
+    for layer, is_v in ((0, False), (2, False), (0, True), (2, True)):
+        got = cache.code_delta_histogram(layer, is_v).cpu().numpy()
+        exp = np.zeros(4, np.int64)
+        for bi in range(2):
+            for h in range(2):
+                st = tl.oracle_slice(w, K, V, bi, h)
+                pre = "v" if is_v else "k"
+                d = np.abs(st[layer][pre + "_codes"].astype(int) - st[layer + 1][pre + "_codes"].astype(int))
+                exp += np.bincount(d.reshape(-1), minlength=4)
+        assert np.array_equal(got, exp), (layer, is_v, got, exp)
+        if not is_v or layer == 0:
+            assert got[:2].sum() / got.sum() > 0.8 and got[3] / got.sum() < 0.05
+    with pytest.raises(XqError) as e:
+        cache.code_delta_histogram(1, True)        # layers 1 (2-bit) and 2 (1-bit) differ in width
+    assert e.value.code == -4
+    cache.close()
