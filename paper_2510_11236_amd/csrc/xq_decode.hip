@@ -128,10 +128,15 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     typedef _Float16 VwT[NV][4][NJ][32 + 8];
     typedef float PartT[NV][D + 2];
     constexpr int KW_BYTES = 4 * (int)sizeof(KwT), PART_BYTES = 4 * (int)sizeof(PartT);
-    __shared__ __attribute__((aligned(16))) char s_raw[(KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES) + 4 * sizeof(VwT)];
+    constexpr int KP_BYTES = KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES;
+    // with several heads the scaled queries live in LDS rather than in 8 registers per head
+    constexpr bool Q_LDS = NV >= 2;
+    typedef float QT[NV][D];
+    __shared__ __attribute__((aligned(16))) char s_raw[KP_BYTES + 4 * sizeof(VwT) + (Q_LDS ? sizeof(QT) : 0)];
     KwT *s_kw = (KwT *)s_raw;
-    VwT *s_vw = (VwT *)(s_raw + (KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES));
+    VwT *s_vw = (VwT *)(s_raw + KP_BYTES);
     PartT *s_part = (PartT *)s_raw;
+    QT &s_q = *(QT *)(s_raw + KP_BYTES + 4 * sizeof(VwT));
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     // 1-D grid, XCD-aware: workgroups go round-robin over the 8 XCDs by linear id, so the
@@ -184,20 +189,25 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     if (split < a.n_splits) {
         // ------------------------------------------------------------ packed tokens
         const int gi = lane / LPG, li = lane % LPG;  // key-weight prep role
-        float qz[NV][CPP];  // q * sm_scale * log2(e) for the channels this lane prepares
+        float qz[Q_LDS ? 1 : NV][CPP];  // q * sm_scale * log2(e) for the channels this lane prepares
         float pw[CPP];      // the code of channel c arrives as c * 2^((BK*c) mod 8 - 24); undo it in the weight
 #pragma unroll
         for (int k = 0; k < CPP; ++k) pw[k] = __builtin_ldexpf(1.0f, 24 - ((BK * (li * CPP + k)) & 7));
         // with few heads a second, pre-shifted copy of q saves a multiply per weight
         constexpr bool QK_COPY = NV == 1;
         float qk[QK_COPY ? NV : 1][CPP];
+        if constexpr (Q_LDS) {
+            for (int idx = tid; idx < NV * D; idx += 256) s_q[idx / D][idx % D] = hbits(qptr(idx / D)[idx % D]) * a.scale_log2e;
+            __syncthreads();
+        } else {
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const uint16_t *qp = qptr(v);
+            for (int v = 0; v < NV; ++v) {
+                const uint16_t *qp = qptr(v);
 #pragma unroll
-            for (int k = 0; k < CPP; ++k) {
-                qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
-                if constexpr (QK_COPY) qk[v][k] = qz[v][k] * pw[k];
+                for (int k = 0; k < CPP; ++k) {
+                    qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
+                    if constexpr (QK_COPY) qk[v][k] = qz[v][k] * pw[k];
+                }
             }
         }
         // Every workgroup starts at a different tile of its range (and wraps around): slices lie
@@ -239,12 +249,14 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     for (int n = 0; n < NREP; ++n) {
                         const int v = y * NREP + n;
                         float zp = 0.f;
-                        float wv[CPP];
+                        float wv[CPP], qv[CPP];
+                        if constexpr (Q_LDS) VecLoad<CPP>::ld((const uint32_t *)&s_q[v][li * CPP], (uint32_t *)qv);
 #pragma unroll
                         for (int k = 0; k < CPP; ++k) {
+                            if constexpr (!Q_LDS) qv[k] = qz[v][k];
                             if constexpr (QK_COPY) wv[k] = qk[v][k] * sh[k];
-                            else wv[k] = qz[v][k] * sh[k];
-                            zp = fmaf(qz[v][k], zh[k], zp);
+                            else wv[k] = qv[k] * sh[k];
+                            zp = fmaf(qv[k], zh[k], zp);
                         }
 #pragma unroll
                         for (int k4 = 0; k4 < CPP; k4 += 4) {
@@ -323,7 +335,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 constexpr int CPB = BYTEK / 4;            // chunks of 4 positions per byte
                 constexpr int NCHUNK = WK * 2 * CPB;
                 constexpr int NSTEP = NCHUNK * NV;
-                constexpr int PF = (NSTEP > 2 && NV != 2) ? 2 : 1;  // NV == 2: one step ahead keeps the kernel at 128 registers
+                constexpr int PF = NSTEP > 2 ? 2 : 1;
                 float4 wl[PF + 1], wh[PF + 1];
                 auto chunk_base = [](int ci) {  // first low-half channel of chunk ci
                     return (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4;
