@@ -325,11 +325,17 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             if constexpr (V_LOAD_EARLY) load_values();
             wave_lds_fence();
             // ---- q . K^ over the packed codes
-            float sc[2][NV], sch[2][NV];  // two chains per score: low-half and high-half channels
+            // Chains per score: low-half and high-half channels, and with several heads also even
+            // and odd positions.  A head step then never reuses an accumulator within 8
+            // instructions; at 4 the compiler pads every reuse with a wait state.
+            constexpr int NCHAIN = NV > 1 ? 2 : 1;
+            float sc[2][NV][NCHAIN], sch[2][NV][NCHAIN];
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int v = 0; v < NV; ++v) sc[s][v] = sch[s][v] = 0.f;
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int e = 0; e < NCHAIN; ++e) sc[s][v][e] = sch[s][v][e] = 0.f;
             const int kg = (row * 32) / G;  // key group of this row inside the tile
             {
                 constexpr int CPB = BYTEK / 4;            // chunks of 4 positions per byte
@@ -370,8 +376,9 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         for (int p = 0; p < 4; ++p)
 #pragma unroll
                             for (int s2 = 0; s2 < 2; ++s2) {
-                                sc[s2][v] = fma_mix_lo(wlo[p], c2[KSH ? 0 : v / NREP][s2][p], sc[s2][v]);
-                                sch[s2][v] = fma_mix_hi(whi[p], c2[KSH ? 0 : v / NREP][s2][p], sch[s2][v]);
+                                float &al = sc[s2][v][p % NCHAIN], &ah = sch[s2][v][p % NCHAIN];
+                                al = fma_mix_lo(wlo[p], c2[KSH ? 0 : v / NREP][s2][p], al);
+                                ah = fma_mix_hi(whi[p], c2[KSH ? 0 : v / NREP][s2][p], ah);
                             }
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
@@ -395,8 +402,13 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             float pr[2][NV];
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                float u0 = row_ok ? (sc[0][v] + sch[0][v]) + zs[v] : -INFINITY;
-                float u1 = row_ok ? (sc[1][v] + sch[1][v]) + zs[v] : -INFINITY;
+                float t0 = sc[0][v][0] + sch[0][v][0], t1 = sc[1][v][0] + sch[1][v][0];
+                if constexpr (NCHAIN == 2) {
+                    t0 += sc[0][v][1] + sch[0][v][1];
+                    t1 += sc[1][v][1] + sch[1][v][1];
+                }
+                float u0 = row_ok ? t0 + zs[v] : -INFINITY;
+                float u1 = row_ok ? t1 + zs[v] : -INFINITY;
                 float tmax = wave_max(fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]));
                 float m_new = fmaxf(m_run[v], tmax);
                 if (m_new > m_run[v]) {  // wave-uniform
