@@ -4,7 +4,7 @@
 A step = one decode step of the whole hot path for every layer: append one new token per
 sequence (with the ring flush when it falls due) and decode attention of one query per head
 over the packed cache + fp16 ring.  Inputs are synthetic, seeded, resident in HBM before the
-timed region.  Prints ONE JSON line (see DESIGN.md "Measurement").
+timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--schedule auto|sequential|fused]
 """
@@ -96,8 +96,8 @@ def main():
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (every (sequence, kv head) slice is independent; "
-              "see DESIGN.md 'How it would shard'); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (every (sequence, kv head) slice is independent, "
+              "so more GPUs would each take a share of the heads with no exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
@@ -249,6 +249,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "xq_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms},
+        "token_head_layers_per_s": w.n_layers * w.batch * w.n_kv_heads * T_mid / (ms_per_step * 1e-3),
         "decode_only_by_schedule": by_schedule,
         "decode_one_call_per_layer_ms": per_layer_ms,
         "append_ms": ms_per_step - decode_ms,

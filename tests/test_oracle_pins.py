@@ -362,6 +362,19 @@ def test_equivalent_bits_golden(oracle):
         assert oracle.equivalent_bits_one(int(L), int(q), int(m)) == float(expect)
 
 
+def test_equivalent_bits_counts_the_stored_layers(oracle):
+    """The paper's examples have as many second layers as first layers in the shared range, so
+    they cannot tell which of the two keeps the codes.  Odd layer counts and odd thresholds can:
+    the accounting must charge exactly the layers the schedule says store codes (the first of a
+    pair; an unpaired last layer keeps its own)."""
+    assert oracle.equivalent_bits_one(3, 3, 0) == pytest.approx(4.0 / 3.0)     # layers 0 and 2 store 2 bits
+    assert oracle.equivalent_bits_one(4, 2, 1) == pytest.approx((2 + 1) / 4)   # layer 0 (2-bit), layer 2 (1-bit)
+    for L, q, m in ((5, 5, 0), (7, 4, 3), (32, 30, 17), (9, 0, 0)):
+        s = oracle.Schedule(L, q, q, m, m, 0.0, 0.0, 32, 128)
+        want = sum(s.bits(l, False) for l in range(L) if s.stores(l, False)) / L
+        assert oracle.equivalent_bits_one(L, q, m) == pytest.approx(want), (L, q, m)
+
+
 # ------------------------------------------------------------------- attention
 def _softmax_attention_ref(q, K, V, sigma):
     u = sigma * (K @ q)
