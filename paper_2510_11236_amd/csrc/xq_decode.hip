@@ -60,35 +60,39 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-template <int N>
+// Global loads.  NT = streaming (non-temporal): for bytes that one workgroup uses once per step,
+// which is everything except codes that a second layer's workgroups read again from L2.
+template <int N, bool NT = true>
 struct VecLoad;
-template <>
-struct VecLoad<1> {
-    static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) { o[0] = *p; }
+template <bool NT>
+struct VecLoad<1, NT> {
+    static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) { o[0] = NT ? __builtin_nontemporal_load(p) : *p; }
 };
-template <>
-struct VecLoad<2> {
+template <bool NT>
+struct VecLoad<2, NT> {
+    typedef uint32_t V __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) {
-        uint2 v = *(const uint2 *)p;
+        V v = NT ? __builtin_nontemporal_load((const V *)p) : *(const V *)p;
         o[0] = v.x;
         o[1] = v.y;
     }
 };
-template <>
-struct VecLoad<4> {
+template <bool NT>
+struct VecLoad<4, NT> {
+    typedef uint32_t V __attribute__((ext_vector_type(4)));
     static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) {
-        uint4 v = *(const uint4 *)p;
+        V v = NT ? __builtin_nontemporal_load((const V *)p) : *(const V *)p;
         o[0] = v.x;
         o[1] = v.y;
         o[2] = v.z;
         o[3] = v.w;
     }
 };
-template <>
-struct VecLoad<8> {
+template <bool NT>
+struct VecLoad<8, NT> {
     static __device__ __forceinline__ void ld(const uint32_t *p, uint32_t *o) {
-        VecLoad<4>::ld(p, o);
-        VecLoad<4>::ld(p + 4, o + 4);
+        VecLoad<4, NT>::ld(p, o);
+        VecLoad<4, NT>::ld(p + 4, o + 4);
     }
 };
 
@@ -98,7 +102,9 @@ __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp
 
 // KSH / VSH: the NLAY layers of a workgroup read one key / value code tensor (a sharing pair);
 // when false each layer has its own codes and only the other tensor's unpacking is shared.
-template <int D, int G, int BK, int BV, int NREP, int NLAY, bool KSH = true, bool VSH = true>
+// REUSE: other workgroups of the launch read the same codes (a sharing layer run one layer per
+// workgroup), so code loads stay ordinary and the second reader finds them in L2.
+template <int D, int G, int BK, int BV, int NREP, int NLAY, bool KSH = true, bool VSH = true, bool REUSE = false>
 __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     constexpr int NKL = KSH ? 1 : NLAY;  // distinct key code tensors per workgroup
     constexpr int NVL = VSH ? 1 : NLAY;
@@ -250,7 +256,10 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         const int v = y * NREP + n;
                         float zp = 0.f;
                         float wv[CPP], qv[CPP];
-                        if constexpr (Q_LDS) VecLoad<CPP>::ld((const uint32_t *)&s_q[v][li * CPP], (uint32_t *)qv);
+                        if constexpr (Q_LDS) {
+#pragma unroll
+                            for (int k = 0; k < CPP; ++k) qv[k] = s_q[v][li * CPP + k];
+                        }
 #pragma unroll
                         for (int k = 0; k < CPP; ++k) {
                             if constexpr (!Q_LDS) qv[k] = qz[v][k];
@@ -280,7 +289,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch) {
-                        if (row_ok) VecLoad<CWK>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[y][s][ch * CWK]);
+                        if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[y][s][ch * CWK]);
                         else {
 #pragma unroll
                             for (int w = 0; w < CWK; ++w) kc[y][s][ch * CWK + w] = 0;
@@ -302,7 +311,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                     for (int kb = 0; kb < 4; ++kb) {
                         const int b2 = tile * 4 + kb;
-                        if (b2 < n_blocks) VecLoad<WS>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[y][kb]);
+                        if (b2 < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[y][kb]);
                         else {
 #pragma unroll
                             for (int w = 0; w < WS; ++w) vc[y][kb][w] = 0;
@@ -638,7 +647,8 @@ hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipSt
             return hipErrorInvalidValue;
         }
     } else {
-        xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(b);
+        if (a.reuse_codes) xq_decode_kernel<D, G, BK, BV, NREP, 1, true, true, true><<<grid, block, 0, s>>>(b);
+        else xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(b);
     }
     return hipGetLastError();
 }

@@ -549,6 +549,10 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.out = (float *)out_f32 + (int64_t)(l - layer0) * per_layer_q;
         a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
+        if (!fused)
+            for (int x = l; x < e; ++x) {
+                a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;
+            }
         if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, rep, e - l, fused, s) != hipSuccess)
             return XQ_ERR_HIP;
         l = e;

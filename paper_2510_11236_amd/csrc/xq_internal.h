@@ -105,6 +105,7 @@ struct XqDecodeArgs {
     int32_t n_launch_z;  // layers (or layer pairs) in this launch; set by the launcher
     int32_t ragged;      // per-sequence lengths seq_T[i] instead of T (Tq follows from the split rule)
     int32_t group;       // g, for the split rule
+    int32_t reuse_codes;  // some layer of the launch reads another layer's codes (keep them in L2)
     int32_t seq_T[XQ_MAX_RAGGED];
 };
 // bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs

@@ -355,7 +355,8 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     const GroupQ qa = group_quant<B>(pair_min(pa), pair_max(pa), c1, c2, &ma);
     const GroupQ qb = group_quant<B>(pair_min(pb), pair_max(pb), c1, c2, &mb);
     uint32_t *mp = (uint32_t *)(a.arena + d.k_meta + (int64_t)bh * a.st.k_meta) + (int64_t)(dst_tok / G) * D + 2 * lane;
-    *(uint2 *)mp = make_uint2(ma, mb);
+    __builtin_nontemporal_store(ma, mp);  // streamed out once: keep it out of the way of the reads
+    __builtin_nontemporal_store(mb, mp + 1);
     if (!d.k_store) return;
     // ---- codes: a word holds 32/B channels of one token = LW lanes x (2 channels x B bits)
     constexpr int LW = 16 / B;             // lanes per word
@@ -389,7 +390,7 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
         for (int k = 1; k < LW; ++k) keep = (lsel == k) ? x[k] : keep;
         // lane (wsel, lsel) holds word wsel of token t0 + lsel
         const int tok = dst_tok + t0 + lsel;
-        cp[(int64_t)(tok / 32) * 32 * W + (wsel / CW) * 32 * CW + (tok % 32) * CW + wsel % CW] = keep;
+        __builtin_nontemporal_store(keep, &cp[(int64_t)(tok / 32) * 32 * W + (wsel / CW) * 32 * CW + (tok % 32) * CW + wsel % CW]);
     }
 }
 
@@ -416,7 +417,7 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
         uint32_t meta;
         const GroupQ q = group_quant<B>(pair_min(mine), pair_max(mine), c1, c2, &meta);
         const int t = c * LPG + i;
-        mp[t * NJ + j] = meta;
+        __builtin_nontemporal_store(meta, &mp[t * NJ + j]);
         s_par[t * NJ + j] = make_float4(q.nmn, q.D1, q.D2, q.D3);
     }
     if (!d.v_store) return;
@@ -448,8 +449,8 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
             words[m] = w;
         }
         uint32_t *wp = cp + (int64_t)(dst_tok / 32 + blk) * 64 * WS + lane * WS;
-        if (WS == 4) *(uint4 *)wp = make_uint4(words[0], words[1], words[2], words[3]);
-        else *(uint2 *)wp = make_uint2(words[0], words[1]);
+#pragma unroll
+        for (int m = 0; m < WS; ++m) __builtin_nontemporal_store(words[m], wp + m);
     }
 }
 
@@ -488,7 +489,7 @@ __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
     }
     uint32_t rows[G];
 #pragma unroll
-    for (int t = 0; t < G; ++t) rows[t] = *(const uint32_t *)(src + t * s_tok + 2 * lane);
+    for (int t = 0; t < G; ++t) rows[t] = __builtin_nontemporal_load((const uint32_t *)(src + t * s_tok + 2 * lane));
     if (!is_v) {
         if (d.bk == 2) pack_keys_wave<G, 2>(a, d, rows, lane, bh, dst_tok);
         else pack_keys_wave<G, 1>(a, d, rows, lane, bh, dst_tok);
