@@ -83,7 +83,7 @@ extern "C" {
 typedef struct xq_config {
     int32_t n_layers;    /* L >= 1 */
     int32_t batch;       /* b >= 1 */
-    int32_t n_q_heads;   /* multiple of n_kv_heads; ratio in {1, 2, 4} (1 when head_dim is 64) */
+    int32_t n_q_heads;   /* multiple of n_kv_heads; ratio at most 16 */
     int32_t n_kv_heads;
     int32_t head_dim;    /* D: 64 or 128 */
     int32_t group;       /* g: 32 or 64, g <= D */

@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 
     auto qptr = [&](int v) -> const uint16_t * {  // query of virtual head v
         int y = v / NREP, n = v % NREP;
-        return a.q + (((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) * D;
+        return a.q + (((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * a.rep + a.q_head0 + n) * D;
     };
 
     float m_run[NV], l_run[NV];
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             }
         }
         const int y = v / NREP, n = v % NREP;
-        float *wp = a.ws + ((((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * NREP + n) *
+        float *wp = a.ws + ((((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * a.rep + a.q_head0 + n) *
                                 (a.n_splits + 1) + split) * (D + 2);
         wp[e] = val;
     }

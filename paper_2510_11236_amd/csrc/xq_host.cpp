@@ -67,8 +67,7 @@ int check_config(const xq_config *c) {
     if (c->group > c->head_dim) return XQ_ERR_UNSUPPORTED;
     if (c->residual < c->group || c->residual % c->group || c->residual > 1024) return XQ_ERR_INVALID_ARG;
     int rep = c->n_q_heads / c->n_kv_heads;
-    if (rep != 1 && rep != 2 && rep != 4) return XQ_ERR_UNSUPPORTED;
-    if (c->head_dim == 64 && rep != 1) return XQ_ERR_UNSUPPORTED;
+    if (rep > XQ_MAX_REP) return XQ_ERR_UNSUPPORTED;
     const int G = group_size(*c);
     if (G < 2 || G > 4) return XQ_ERR_INVALID_ARG;
     if (c->share_dominant < 0 || c->share_dominant >= G) return XQ_ERR_INVALID_ARG;
@@ -502,6 +501,13 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
     const int64_t per_layer_q = (int64_t)c.batch * c.n_q_heads * c.head_dim;
     const int64_t per_layer_ws = (int64_t)c.batch * c.n_q_heads * (n_splits + 1) * (c.head_dim + 2);
     const int rep = c.n_q_heads / c.n_kv_heads;
+    // The kernels serve 1, 2 or 4 query heads of a kv head at a time (1 when D = 64): other
+    // ratios take several passes over the kv head's cache, largest part first.
+    int parts[XQ_MAX_REP], n_parts = 0;
+    for (int left = rep; left > 0; left -= parts[n_parts++])
+        parts[n_parts] = (c.head_dim == 64) ? 1 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1));
+    bool fusable = true;  // a pair shares a workgroup only if every part fits the kernel's weight tables
+    for (int i = 0; i < n_parts; ++i) fusable = fusable && xq_decode_can_fuse(c.head_dim, c.group, parts[i]);
     // runs of layers with one (bk, bv) and one fusion mode share a launch
     int l = layer0;
     while (l < layer0 + n_layers) {
@@ -509,7 +515,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         // sharing mode of the pair (a, a+1) when one workgroup may serve it: bit 0 keys shared,
         // bit 1 values shared; 0 = not fusable
         auto fuse_mode = [&](int a) -> int {
-            if (!(flags & XQ_DECODE_PAIR_FUSED) || !xq_decode_can_fuse(c.head_dim, c.group, rep)) return 0;
+            if (!(flags & XQ_DECODE_PAIR_FUSED) || !fusable) return 0;
             if (group_size(c) != 2 || c.share_dominant != 0) return 0;
             if (a % 2 != 0 || a + 1 >= layer0 + n_layers) return 0;
             if (cache->layers[a + 1].bk != cache->layers[a].bk || cache->layers[a + 1].bv != cache->layers[a].bv) return 0;
@@ -553,8 +559,13 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;
             }
-        if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, rep, e - l, fused, s) != hipSuccess)
-            return XQ_ERR_HIP;
+        a.rep = rep;
+        for (int i = 0; i < n_parts; ++i) {
+            if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, parts[i], e - l, fused, s) != hipSuccess)
+                return XQ_ERR_HIP;
+            a.q_head0 += parts[i];
+        }
+        if (xq_launch_merge(a, c.head_dim, e - l, s) != hipSuccess) return XQ_ERR_HIP;
         l = e;
     }
     return XQ_OK;

@@ -10,7 +10,8 @@
 #define XQ_MAX_LAYERS 256
 #define XQ_MAX_SPLITS 64     // packed-token splits per (layer, sequence, kv head)
 #define XQ_TILE_TOKENS 128   // tokens one wave handles per iteration of the decode loop
-#define XQ_MAX_RAGGED 256    // largest batch whose sequences may have different lengths
+#define XQ_MAX_RAGGED 256
+#define XQ_MAX_REP 16  /* query heads per kv head */    // largest batch whose sequences may have different lengths
 
 // Where a layer's regions live inside the arena (byte offsets) and what it holds.
 // k_codes / v_codes point at the codes the layer READS: its own, or those of the
@@ -105,12 +106,16 @@ struct XqDecodeArgs {
     int32_t n_launch_z;  // layers (or layer pairs) in this launch; set by the launcher
     int32_t ragged;      // per-sequence lengths seq_T[i] instead of T (Tq follows from the split rule)
     int32_t group;       // g, for the split rule
+    int32_t rep, q_head0;  // query heads per kv head; first of them that this launch serves (it serves n_rep)
     int32_t reuse_codes;  // some layer of the launch reads another layer's codes (keep them in L2)
     int32_t seq_T[XQ_MAX_RAGGED];
 };
-// bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs
+// bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs;
+// n_rep in {1, 2, 4}: query heads q_head0 .. q_head0 + n_rep - 1 of every kv head.
+// Writes the split partials; xq_launch_merge turns them into the outputs.
 hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv, int n_rep,
                             int n_layers, int pair_fused, hipStream_t s);
+hipError_t xq_launch_merge(const XqDecodeArgs &a, int D, int n_layers, hipStream_t s);
 
 bool xq_decode_can_fuse(int D, int g, int n_rep);
 

@@ -43,7 +43,10 @@ hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv,
     XQ_CASE_BITS(128, 64)
     XQ_CASE_BITS(64, 32)
     XQ_CASE_BITS(64, 64)
-    if (e != hipSuccess) return e;
+    return e;
+}
+
+hipError_t xq_launch_merge(const XqDecodeArgs &a, int D, int n_layers, hipStream_t s) {
     const int64_t heads = (int64_t)n_layers * a.batch * a.n_q_heads;
     if (D == 128) xq_merge_kernel<128><<<dim3((unsigned)heads), dim3(128), 0, s>>>(a.ws, a.out, a.n_splits + 1);
     else xq_merge_kernel<64><<<dim3((unsigned)heads), dim3(64), 0, s>>>(a.ws, a.out, a.n_splits + 1);

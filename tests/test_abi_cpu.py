@@ -45,9 +45,8 @@ def _cfg(xq, **kw):
 def test_config_validation(xq):
     assert xq.cache_bytes(_cfg(xq))[0] > 0
     for bad, code in [(dict(head_dim=96), -2), (dict(group=16), -2), (dict(residual=100), -1), (dict(eta1=0.5), -1),
-                      (dict(eta2=-0.1), -1), (dict(n_q_heads=48), -1), (dict(n_q_heads=32, n_kv_heads=2), -2),
-                      (dict(n_layers=0), -1), (dict(kq=31, km=0), -1), (dict(vq=1, vm=0), -1),
-                      (dict(head_dim=64, n_q_heads=32, n_kv_heads=8), -2)]:
+                      (dict(eta2=-0.1), -1), (dict(n_q_heads=48), -1), (dict(n_q_heads=34, n_kv_heads=2), -2),
+                      (dict(n_layers=0), -1), (dict(kq=31, km=0), -1), (dict(vq=1, vm=0), -1)]:
         with pytest.raises(xq.XqError) as e:
             xq.cache_bytes(_cfg(xq, **bad))
         assert e.value.code == code, bad

@@ -75,6 +75,18 @@ def test_d128_variants(lib_, g, R, kq, vq, km, vm, rep):
     print("variant worst attention error", worst)
 
 
+@pytest.mark.parametrize("D,g,rep,km", [(128, 32, 3, 0), (128, 32, 7, 0), (128, 64, 8, 0), (128, 64, 5, 4),
+                                        (128, 32, 6, 4), (64, 32, 2, 0), (64, 32, 3, 4)])
+def test_query_heads_per_kv_head(lib_, D, g, rep, km):
+    """Any number of query heads per kv head: the heads of a kv head are served in parts of
+    4, 2 and 1 (1 when D = 64), sequential and pair-fused schedules."""
+    base = synth.workloads()[1 if D == 128 else 0]
+    w = synth.scaled(base, n_layers=4, batch=2, n_q_heads=2 * rep, n_kv_heads=2, group=g, residual=2 * g,
+                     kq=4, vq=4, km=km, vm=km, eta1=1 / 6, eta2=0.045, seed=50 + rep)
+    worst = _run_prefill_case(lib_, w, 700, tps_list=(0, 2))
+    print("rep", rep, "worst attention error", worst)
+
+
 def test_peaked_attention(lib_):
     """Queries aligned with one cached key: few tokens carry the weight, the regime where
     score errors show most."""
