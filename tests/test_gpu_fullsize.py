@@ -212,3 +212,14 @@ def test_paper_main_schedule_full_size(tl):
 
     worst = _run_full_mixed(tl, w, sample_layers=[(0, 1), (14, 15), (16, 17), (30, 31)], sample_bh=[(0, 0), (3, 31)])
     print("paper main schedule worst attention error", worst)
+
+
+def test_long_context_256k(tl):
+    """One sequence of 262 221 tokens (ragged last tile, ring not full): the longest single
+    sequence the split plan sees here (2048 tiles over 64 splits); offsets inside a slice pass
+    2^25 bytes and the per-layer regions 2^28."""
+    base = synth.workloads()[2]
+    w = synth.scaled(base, name="long_256k", n_layers=2, batch=1, n_q_heads=8, n_kv_heads=8, context=262144 + 77 - 3,
+                     seed=77)
+    worst = _run_full(tl, w, n_append=3, check_steps={3}, sample_pairs={0}, sample_bh=[(0, 0), (0, 7)])
+    print("256k context worst attention error", worst)
