@@ -214,6 +214,18 @@ def test_paper_main_schedule_full_size(tl):
     print("paper main schedule worst attention error", worst)
 
 
+def test_llama_row_schedule(tl):
+    """kq=28, vq=0, km=32, vm=28 (the Llama2-7b row of the paper's configuration table, 1.40625
+    equivalent bits) at that model's 8192-token limit, and the Mistral GQA shape (32 query heads
+    over 8 kv heads) with the main schedule kq=30, vq=2, km=32, vm=16 at its 30000-token limit."""
+    base = synth.workloads()[5]
+    w = synth.scaled(base, name="llama_row_8k_b4", context=8192, kq=28, vq=0, km=32, vm=28, seed=28)
+    worst = _run_full_mixed(tl, w, sample_layers=[(0, 1), (26, 27), (28, 29), (30, 31)], sample_bh=[(1, 5), (3, 30)])
+    w = synth.scaled(base, name="mistral_gqa_30k_b4", context=30000, n_kv_heads=8, seed=30)
+    worst = max(worst, _run_full_mixed(tl, w, sample_layers=[(0, 1), (16, 17), (30, 31)], sample_bh=[(0, 7), (2, 3)]))
+    print("configuration-table schedules worst attention error", worst)
+
+
 def test_long_context_256k(tl):
     """One sequence of 262 221 tokens (ragged last tile, ring not full): the longest single
     sequence the split plan sees here (2048 tiles over 64 splits); offsets inside a slice pass
