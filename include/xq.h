@@ -166,8 +166,9 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * q_f16: device fp16 [n_layers][batch][n_q_heads][D]; out_f32: device fp32, same shape.
  * dev_workspace: device scratch, at least the size xq_cache_bytes reported (less is accepted
  * when it suffices for the current lengths).  flags: 0, or XQ_DECODE_PAIR_FUSED to let one
- * workgroup serve both layers of a sharing pair so that their common codes are fetched once
- * (the result is the same up to fp32 summation order).  All layers in the range must hold
+ * workgroup serve both layers of a pair that shares key and value codes, so that the common
+ * codes are fetched and unpacked once (the result is the same up to fp32 summation order; pairs
+ * that share only one of the two, or not at all, run one layer per workgroup as without it).  All layers in the range must hold
  * the same, non-zero number of tokens per sequence (sequences may differ from one another). */
 #define XQ_DECODE_PAIR_FUSED 1
 int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,

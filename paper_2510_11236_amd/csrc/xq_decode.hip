@@ -100,14 +100,10 @@ struct VecLoad<8, NT> {
 // come out as 0, which is what a weight of 2^-126 may be.
 __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// KSH / VSH: the NLAY layers of a workgroup read one key / value code tensor (a sharing pair);
-// when false each layer has its own codes and only the other tensor's unpacking is shared.
-// REUSE: other workgroups of the launch read the same codes (a sharing layer run one layer per
-// workgroup), so code loads stay ordinary and the second reader finds them in L2.
-template <int D, int G, int BK, int BV, int NREP, int NLAY, bool KSH = true, bool VSH = true, bool REUSE = false>
+// NLAY = 2: the two layers of a sharing pair (one key and one value code tensor, read by the
+// first layer's descriptor) are served by one workgroup.
+template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false>
 __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
-    constexpr int NKL = KSH ? 1 : NLAY;  // distinct key code tensors per workgroup
-    constexpr int NVL = VSH ? 1 : NLAY;
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane
     constexpr int NJ = D / G;             // value groups per token
@@ -279,20 +275,19 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 }
             }
             // ---- this lane's two key rows (tokens r16 and r16 + 16 of block blk)
-            uint32_t kc[NKL][2][WK];
-#pragma unroll
-            for (int y = 0; y < NKL; ++y) {
-                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[y].k_codes +
+            uint32_t kc[2][WK];
+            {
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
                                                         (int64_t)bh * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
                                      (int64_t)blk * 32 * WK;
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch) {
-                        if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[y][s][ch * CWK]);
+                        if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
                         else {
 #pragma unroll
-                            for (int w = 0; w < CWK; ++w) kc[y][s][ch * CWK + w] = 0;
+                            for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
                         }
                     }
             }
@@ -301,20 +296,19 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             // they are issued after it, which keeps 32+ registers free during the key loop (one
             // more wave per SIMD) at the cost of latency that the other waves cover.
             constexpr bool V_LOAD_EARLY = NV == 1;
-            uint32_t vc[NVL][4][WS];
+            uint32_t vc[4][WS];
             uint32_t vm[NLAY][2][NJ];
             auto load_values = [&]() {
-#pragma unroll
-                for (int y = 0; y < NVL; ++y) {
-                    const uint32_t *cp = (const uint32_t *)(a.arena + dsc[y].v_codes +
+                {
+                    const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
                                                             (int64_t)bh * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
                     for (int kb = 0; kb < 4; ++kb) {
                         const int b2 = tile * 4 + kb;
-                        if (b2 < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[y][kb]);
+                        if (b2 < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[kb]);
                         else {
 #pragma unroll
-                            for (int w = 0; w < WS; ++w) vc[y][kb][w] = 0;
+                            for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
                         }
                     }
                 }
@@ -365,15 +359,13 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int ci = 0; ci < NCHUNK; ++ci) {
                     const int wi = ci / (2 * CPB), src = (ci / CPB) % 2, p4 = (ci % CPB) * 4;
-                    uint32_t c2[NKL][2][4];
+                    uint32_t c2[2][4];
 #pragma unroll
-                    for (int y = 0; y < NKL; ++y)
-#pragma unroll
-                        for (int s2 = 0; s2 < 2; ++s2) {
-                            const uint32_t x = src ? (kc[y][s2][wi] >> 8) : kc[y][s2][wi];
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                            const uint32_t x = src ? (kc[s2][wi] >> 8) : kc[s2][wi];
 #pragma unroll
                             for (int p = 0; p < 4; ++p)
-                                c2[y][s2][p] = x & (MASKK << (BK * (p4 + p)));
+                                c2[s2][p] = x & (MASKK << (BK * (p4 + p)));
                         }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
@@ -386,8 +378,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                             for (int s2 = 0; s2 < 2; ++s2) {
                                 float &al = sc[s2][v][p % NCHAIN], &ah = sch[s2][v][p % NCHAIN];
-                                al = fma_mix_lo(wlo[p], c2[KSH ? 0 : v / NREP][s2][p], al);
-                                ah = fma_mix_hi(whi[p], c2[KSH ? 0 : v / NREP][s2][p], ah);
+                                al = fma_mix_lo(wlo[p], c2[s2][p], al);
+                                ah = fma_mix_hi(whi[p], c2[s2][p], ah);
                             }
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
@@ -469,16 +461,14 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int ci = 0; ci < NCHUNK; ++ci) {
                     const int kb = ci / (WS * VCH), m = (ci / VCH) % WS, i0 = (ci % VCH) * 4;
-                    half2_t c2[NVL][4][CPL];
+                    half2_t c2[4][CPL];
 #pragma unroll
-                    for (int y = 0; y < NVL; ++y)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < 4; ++i)
 #pragma unroll
                             for (int c = 0; c < CPL; ++c) {
                                 const int bit = BV * ((i0 + i) * CPL + c);   // position inside a half, < 16
-                                const uint32_t x = (bit >= 8) ? (vc[y][kb][m] >> 8) : vc[y][kb][m];
-                                c2[y][i][c] = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
+                                const uint32_t x = (bit >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                                c2[i][c] = __builtin_bit_cast(half2_t, x & (MASKV << (bit & 7)));
                             }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
@@ -491,7 +481,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         for (int i = 0; i < 4; ++i)
 #pragma unroll
                             for (int c = 0; c < CPL; ++c)
-                                accv[v][c] = __builtin_amdgcn_fdot2(w2[i], c2[VSH ? 0 : v / NREP][i][c], accv[v][c], false);
+                                accv[v][c] = __builtin_amdgcn_fdot2(w2[i], c2[i][c], accv[v][c], false);
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -636,18 +626,14 @@ hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipSt
     b.n_launch_z = pair_fused ? n_layers / 2 : n_layers;
     dim3 grid((unsigned)((a.n_splits + 1) * a.batch * a.n_kv_heads * b.n_launch_z));
     if (pair_fused) {
-        // pair_fused bits: 1 = keys shared, 2 = values shared.
         // 2 * NREP virtual heads must fit the LDS weight tables
         if constexpr (2 * NREP * (XQ_TILE_TOKENS / G) <= 16 && (D == 128 || NREP == 1)) {
-            if (pair_fused == 3) xq_decode_kernel<D, G, BK, BV, NREP, 2, true, true><<<grid, block, 0, s>>>(b);
-            else if (pair_fused == 2) xq_decode_kernel<D, G, BK, BV, NREP, 2, false, true><<<grid, block, 0, s>>>(b);
-            else if (pair_fused == 1) xq_decode_kernel<D, G, BK, BV, NREP, 2, true, false><<<grid, block, 0, s>>>(b);
-            else return hipErrorInvalidValue;
+            xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(b);
         } else {
             return hipErrorInvalidValue;
         }
     } else {
-        if (a.reuse_codes) xq_decode_kernel<D, G, BK, BV, NREP, 1, true, true, true><<<grid, block, 0, s>>>(b);
+        if (a.reuse_codes) xq_decode_kernel<D, G, BK, BV, NREP, 1, true><<<grid, block, 0, s>>>(b);
         else xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(b);
     }
     return hipGetLastError();

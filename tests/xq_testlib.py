@@ -81,7 +81,11 @@ def check_attention(out, w, ref, bi, h, atol=ATOL):
         assert np.all(np.isfinite(got)), f"layer {l} non-finite output"
         err = float(np.max(np.abs(got - r)))
         worst = max(worst, err)
-        assert err <= atol, f"layer {l} slice ({bi},{h}): max abs err {err:.3e} > {atol}"
+        if err > atol:
+            bad = np.argwhere(np.abs(got - r) > atol)
+            raise AssertionError(f"layer {l} slice ({bi},{h}): max abs err {err:.3e} > {atol}; {len(bad)} of "
+                                 f"{got.size} outputs off, first (head, channel): {bad[:8].tolist()}, "
+                                 f"got {got[tuple(bad[0])]:.5f} want {r[tuple(bad[0])]:.5f}")
     return worst
 
 
