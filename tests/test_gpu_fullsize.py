@@ -206,8 +206,8 @@ def test_cfg4_prefill_pack_then_64_decode_steps(tl):
 
 def test_paper_main_schedule_full_size(tl):
     """kq=30, vq=2, km=32, vm=16 (the paper's main configuration, 1.375 equivalent bits): keys
-    never shared, values 1-bit and shared from layer 16 on; mixed bit widths inside one call and
-    value-only sharing in the fused schedule."""
+    never shared, values 1-bit and shared from layer 16 on; mixed bit widths inside one call, and
+    a fused-schedule request that must fall back to one layer per workgroup (values-only sharing)."""
     w = synth.workloads()[5]
 
     worst = _run_full_mixed(tl, w, sample_layers=[(0, 1), (14, 15), (16, 17), (30, 31)], sample_bh=[(0, 0), (3, 31)])
