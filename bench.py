@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "fused"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-slices", type=int, default=24)
+    ap.add_argument("--cpu-slices", type=int, default=96)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
