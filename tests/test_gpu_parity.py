@@ -450,3 +450,41 @@ def test_code_delta_histogram(lib_):
         cache.code_delta_histogram(1, True)        # layers 1 (2-bit) and 2 (1-bit) differ in width
     assert e.value.code == -4
     cache.close()
+
+
+@pytest.mark.parametrize("D,g,bits", [(128, 32, 2), (128, 64, 1), (128, 32, 1), (64, 32, 2), (64, 64, 1)])
+def test_pack_random_bit_patterns(lib_, D, g, bits):
+    """Stored codes and metadata, bit for bit, on inputs drawn as random fp16 bit patterns (every
+    exponent up to 2^13, subnormals, both zeros): scales from 2^-24 to 10^4 inside one tensor,
+    groups with one huge outlier, near-ties everywhere.  Exercises the division-free code
+    thresholds of the wave kernel (D = 128) and the per-element division of the general kernel
+    (D = 64) against the oracle's IEEE division."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[1 if D == 128 else 0], n_layers=2, batch=2, n_q_heads=2, n_kv_heads=2,
+                     head_dim=D, group=g, residual=g, kq=2 * (bits == 2), vq=2 * (bits == 2), km=0, vm=2,
+                     eta1=1 / 6, eta2=0.045)
+    T = 8 * g + 5
+    gen = torch.Generator().manual_seed(D + g + bits)
+
+    def patterns(shape):
+        raw = torch.randint(0, 1 << 16, shape, generator=gen, dtype=torch.int32)
+        expo = (raw >> 10) & 0x1f
+        raw = torch.where(expo > 28, raw & ~(0x1f << 10) | (torch.randint(0, 29, shape, generator=gen, dtype=torch.int32) << 10), raw)
+        x = raw.to(torch.uint16).view(torch.float16)
+        # half of the groups: confine the exponent spread so that codes other than 0 and n occur
+        narrow = (torch.randint(0, 1 << 15, shape, generator=gen, dtype=torch.int32) & 0x83ff | (15 << 10)).to(torch.uint16).view(torch.float16)
+        pick = torch.rand(shape[:-2] + (1, 1), generator=gen) < 0.5
+        return torch.where(pick, narrow, x)
+
+    K = patterns((w.n_layers, w.batch, w.n_kv_heads, T, D))
+    V = patterns((w.n_layers, w.batch, w.n_kv_heads, T, D))
+    assert torch.isfinite(K.float()).all() and torch.isfinite(V.float()).all()
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(K.cuda(), V.cuda())
+    torch.cuda.synchronize()
+    for bi in range(w.batch):
+        for h in range(w.n_kv_heads):
+            st = tl.oracle_slice(w, K, V, bi, h)
+            tl.check_stored(cache, w, st, bi, h)
+            tl.check_unpack(cache, w, st, bi, h)
+    cache.close()
