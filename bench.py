@@ -86,8 +86,8 @@ def cpu_baseline(w, slices, q_cpu, sigma, T):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "fused"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
