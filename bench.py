@@ -71,6 +71,10 @@ def cpu_baseline(w, slices, q_cpu, sigma, T):
         return orc.decode_slice(j[0], j[1], j[2], j[3], sigma)
 
     run(jobs[0])
+    t1 = time.perf_counter()
+    for j in jobs[:4]:
+        run(j)
+    one_core = 4 / (time.perf_counter() - t1)        # slice-layers per second on one thread
     t0 = time.perf_counter()
     with ThreadPoolExecutor(max_workers=threads) as ex:
         list(ex.map(run, jobs))
@@ -78,6 +82,7 @@ def cpu_baseline(w, slices, q_cpu, sigma, T):
     slice_layers_per_s = len(jobs) / dt
     t_step = w.n_layers * w.batch * w.n_kv_heads / slice_layers_per_s
     return {"value": w.batch * T / t_step, "unit": "KV tokens/s", "cores": threads, "kind": "oracle",
+            "one_core_value": w.batch * T / (w.n_layers * w.batch * w.n_kv_heads / one_core),
             "sample": f"{len(jobs)} (layer, sequence, kv-head) slices of the first layer pair at T={T}, "
                       f"dequantize+attention in fp64, {dt:.1f} s wall, scaled linearly to all "
                       f"{w.n_layers * w.batch * w.n_kv_heads} slices"}
