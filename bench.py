@@ -58,14 +58,20 @@ def cpu_baseline(w, slices, q_cpu, sigma, T):
     sch = orc.Schedule(w.n_layers, w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.group, w.residual)
     rep = w.n_q_heads // w.n_kv_heads
     jobs = []
-    for (bi, h), (K2, V2) in slices.items():
-        # a pair on its own is a 2-layer model with the pair's schedule
-        sch2 = orc.Schedule(2, 2 if w.kq > 0 else 0, 2 if w.vq > 0 else 0, 0 if w.km < w.n_layers else 2,
-                            0 if w.vm < w.n_layers else 2, w.eta1, w.eta2, w.group, w.residual)
-        st = orc.cache_slice(sch2, K2, V2)
+    # a pair on its own is a 2-layer model with the pair's schedule
+    sch2 = orc.Schedule(2, 2 if w.kq > 0 else 0, 2 if w.vq > 0 else 0, 0 if w.km < w.n_layers else 2,
+                        0 if w.vm < w.n_layers else 2, w.eta1, w.eta2, w.group, w.residual)
+    keys = list(slices)
+    threads = min(2 * len(keys), os.cpu_count() or 1, 16)
+    orc.lib()
+    tp = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:       # quantization phase (the pack leg)
+        states = list(ex.map(lambda k: orc.cache_slice(sch2, slices[k][0], slices[k][1]), keys))
+    pack_s = time.perf_counter() - tp
+    pack_bytes = sum(slices[k][0].nbytes + slices[k][1].nbytes for k in keys)
+    for (bi, h), st in zip(keys, states):
         for l in (0, 1):
             jobs.append((sch2, st, l, q_cpu[l, bi, h * rep:(h + 1) * rep].numpy().view(np.uint16)))
-    threads = min(len(jobs), os.cpu_count() or 1, 16)
 
     def run(j):
         return orc.decode_slice(j[0], j[1], j[2], j[3], sigma)
@@ -82,6 +88,7 @@ def cpu_baseline(w, slices, q_cpu, sigma, T):
     slice_layers_per_s = len(jobs) / dt
     t_step = w.n_layers * w.batch * w.n_kv_heads / slice_layers_per_s
     return {"value": w.batch * T / t_step, "unit": "KV tokens/s", "cores": threads, "kind": "oracle",
+            "pack_GBps_fp16_read": pack_bytes / pack_s / 1e9,
             "one_core_value": w.batch * T / (w.n_layers * w.batch * w.n_kv_heads / one_core),
             "sample": f"{len(jobs)} (layer, sequence, kv-head) slices of the first layer pair at T={T}, "
                       f"dequantize+attention in fp64, {dt:.1f} s wall, scaled linearly to all "
@@ -133,7 +140,10 @@ def main():
     Ttot = T0 + n_extra
     new_k = torch.empty((n_extra, w.n_layers, w.batch, w.n_kv_heads, w.head_dim), dtype=torch.float16, device=dev)
     new_v = torch.empty_like(new_k)
-    sample = [(i % w.batch, (7 * i + 3) % w.n_kv_heads) for i in range(args.cpu_slices)]
+    # distinct (sequence, kv head) slices for the oracle baseline, spread over the batch and the heads
+    nbh = w.batch * w.n_kv_heads
+    stride = next(s for s in (37, 41, 43, 47, 53, 1) if np.gcd(s, nbh) == 1)
+    sample = [divmod((3 + stride * i) % nbh, w.n_kv_heads) for i in range(min(args.cpu_slices, nbh))]
     slices = {}
     pack_ms, pack_bytes = 0.0, 0
     pend = []
