@@ -334,14 +334,23 @@ __device__ __forceinline__ uint32_t push_code(uint32_t w, float d, const GroupQ 
     return w;
 }
 
+// Merged code of a sharing pair (Appendix E): e_m = lut[(e_0, e_1)] from the two layers' own
+// codes of one element, d0 / d1 = x - min in each layer's own group.
+template <int B>
+__device__ __forceinline__ uint32_t merged_code(float d0, const GroupQ &q0, float d1, const GroupQ &q1, uint32_t lut) {
+    const uint32_t e = push_code<B>(push_code<B>(0u, d0, q0), d1, q1);  // (e_0 << B) | e_1
+    return (lut >> (B * e)) & ((1u << B) - 1u);
+}
+
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_or(uint32_t x) {
     return x | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
 }
 
-template <int G, int B>
+// MG: the stored codes are merged with the next layer's own codes, whose rows are rows2.
+template <int G, int B, bool MG>
 __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
-                                               int lane, int bh, int dst_tok) {
+                                               const uint32_t (&rows2)[MG ? G : 1], int lane, int bh, int dst_tok) {
     constexpr int D = 128;
     // ---- per-channel min / max down the g tokens (two channels per lane)
     uint32_t pa = 0x7c007c00u, pb = 0x7c007c00u;  // (+inf, +inf)
@@ -358,6 +367,19 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     __builtin_nontemporal_store(ma, mp);  // streamed out once: keep it out of the way of the reads
     __builtin_nontemporal_store(mb, mp + 1);
     if (!d.k_store) return;
+    GroupQ q2a = qa, q2b = qb;  // the next layer's own groups (its metadata is written by its own wave)
+    if constexpr (MG) {
+        uint32_t pa2 = 0x7c007c00u, pb2 = 0x7c007c00u;
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+            pa2 = minmax_lo(pa2, rows2[t]);
+            pb2 = minmax_hi(pb2, rows2[t]);
+        }
+        uint32_t unused;
+        q2a = group_quant<B>(pair_min(pa2), pair_max(pa2), c1, c2, &unused);
+        q2b = group_quant<B>(pair_min(pb2), pair_max(pb2), c1, c2, &unused);
+    }
+    const uint32_t lut = B == 2 ? a.lut2 : a.lut1;
     // ---- codes: a word holds 32/B channels of one token = LW lanes x (2 channels x B bits)
     constexpr int LW = 16 / B;             // lanes per word
     constexpr int W = D * B / 32;          // words per token row
@@ -371,8 +393,14 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
         uint32_t x[LW];
 #pragma unroll
         for (int k = 0; k < LW; ++k) {
-            uint32_t nib = push_code<B>(0u, sub_hi(rows[t0 + k], qb.nmn), qb);
-            nib = push_code<B>(nib, sub_lo(rows[t0 + k], qa.nmn), qa);
+            uint32_t nib;
+            if constexpr (MG) {
+                nib = merged_code<B>(sub_hi(rows[t0 + k], qb.nmn), qb, sub_hi(rows2[t0 + k], q2b.nmn), q2b, lut) << B;
+                nib |= merged_code<B>(sub_lo(rows[t0 + k], qa.nmn), qa, sub_lo(rows2[t0 + k], q2a.nmn), q2a, lut);
+            } else {
+                nib = push_code<B>(0u, sub_hi(rows[t0 + k], qb.nmn), qb);
+                nib = push_code<B>(nib, sub_lo(rows[t0 + k], qa.nmn), qa);
+            }
             x[k] = nib << (2 * B * lsel);
         }
 #pragma unroll
@@ -394,9 +422,10 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     }
 }
 
-template <int G, int B>
+template <int G, int B, bool MG>
 __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
-                                                 int lane, int bh, int dst_tok, float4 *s_par) {
+                                                 const uint32_t (&rows2)[MG ? G : 1], int lane, int bh, int dst_tok,
+                                                 float4 *s_par, float4 *s_par2) {
     constexpr int D = 128, NJ = D / G, LPG = G / 2;  // lanes per channel group
     const int j = lane / LPG, i = lane % LPG;
     const float c1 = B == 2 ? a.c1_2 : a.c1_1, c2 = B == 2 ? a.c2_2 : a.c2_1;
@@ -419,8 +448,23 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
         const int t = c * LPG + i;
         __builtin_nontemporal_store(meta, &mp[t * NJ + j]);
         s_par[t * NJ + j] = make_float4(q.nmn, q.D1, q.D2, q.D3);
+        if constexpr (MG) {  // the next layer's own group of the same token
+            uint32_t mine2 = 0;
+#pragma unroll
+            for (int k = 0; k < LPG; ++k) {
+                const int t2 = c * LPG + k;
+                uint32_t p = minmax_hi(minmax_lo(0x7c007c00u, rows2[t2]), rows2[t2]);
+#pragma unroll
+                for (int o = 1; o < LPG; o <<= 1) p = pk_min(p, (uint32_t)__shfl_xor((int)p, o, 64));
+                mine2 = (i == k) ? p : mine2;
+            }
+            uint32_t unused;
+            const GroupQ q2 = group_quant<B>(pair_min(mine2), pair_max(mine2), c1, c2, &unused);
+            s_par2[t * NJ + j] = make_float4(q2.nmn, q2.D1, q2.D2, q2.D3);
+        }
     }
     if (!d.v_store) return;
+    const uint32_t lut = B == 2 ? a.lut2 : a.lut1;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -443,8 +487,19 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
                 q.D1 = f.y;
                 q.D2 = f.z;
                 q.D3 = f.w;
-                w = push_code<B>(w, sub_hi(rows[t], q.nmn), q);
-                w = push_code<B>(w, sub_lo(rows[t], q.nmn), q);
+                if constexpr (MG) {
+                    const float4 f2 = s_par2[t * NJ + j];
+                    GroupQ q2;
+                    q2.nmn = f2.x;
+                    q2.D1 = f2.y;
+                    q2.D2 = f2.z;
+                    q2.D3 = f2.w;
+                    w = (w << B) | merged_code<B>(sub_hi(rows[t], q.nmn), q, sub_hi(rows2[t], q2.nmn), q2, lut);
+                    w = (w << B) | merged_code<B>(sub_lo(rows[t], q.nmn), q, sub_lo(rows2[t], q2.nmn), q2, lut);
+                } else {
+                    w = push_code<B>(w, sub_hi(rows[t], q.nmn), q);
+                    w = push_code<B>(w, sub_lo(rows[t], q.nmn), q);
+                }
             }
             words[m] = w;
         }
@@ -457,10 +512,13 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
 // grid.x = 2 * token groups (first half: keys, second half: values -- kept apart because
 // workgroups are dealt round-robin to the 8 XCDs and the two kinds cost differently),
 // grid.y = sequence * kv head, grid.z = layer
-template <int G>
+// MG: built for caches whose sharing pairs store merged codes (Appendix E); a wave of the
+// pair's first layer then also reads the second layer's rows.
+template <int G, bool MG = false>
 __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
     constexpr int D = 128;
     __shared__ float4 s_par[G * (D / G)];
+    __shared__ float4 s_par2[MG ? G * (D / G) : 1];
     const int lane = threadIdx.x;
     const bool is_v = (int)blockIdx.x >= a.n_groups;
     const int grp = is_v ? blockIdx.x - a.n_groups : blockIdx.x;
@@ -490,12 +548,36 @@ __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
     uint32_t rows[G];
 #pragma unroll
     for (int t = 0; t < G; ++t) rows[t] = __builtin_nontemporal_load((const uint32_t *)(src + t * s_tok + 2 * lane));
+    const uint32_t none[1] = {0};
+    if constexpr (MG) {
+        if (is_v ? d.v_merge : d.k_merge) {  // uniform over the wave
+            const uint16_t *src2;
+            if (a.from_ring) {
+                const XqLayerDesc d2 = a.layers[a.layer0 + lz + 1];
+                src2 = (const uint16_t *)(a.arena + (is_v ? d2.v_res : d2.k_res) + (int64_t)bh * a.st.res) +
+                       (int64_t)(src_tok0 + grp * G) * D;
+            } else {
+                src2 = src + a.s_layer;
+            }
+            uint32_t rows2[G];
+#pragma unroll
+            for (int t = 0; t < G; ++t) rows2[t] = __builtin_nontemporal_load((const uint32_t *)(src2 + t * s_tok + 2 * lane));
+            if (!is_v) {
+                if (d.bk == 2) pack_keys_wave<G, 2, true>(a, d, rows, rows2, lane, bh, dst_tok);
+                else pack_keys_wave<G, 1, true>(a, d, rows, rows2, lane, bh, dst_tok);
+            } else {
+                if (d.bv == 2) pack_values_wave<G, 2, true>(a, d, rows, rows2, lane, bh, dst_tok, s_par, s_par2);
+                else pack_values_wave<G, 1, true>(a, d, rows, rows2, lane, bh, dst_tok, s_par, s_par2);
+            }
+            return;
+        }
+    }
     if (!is_v) {
-        if (d.bk == 2) pack_keys_wave<G, 2>(a, d, rows, lane, bh, dst_tok);
-        else pack_keys_wave<G, 1>(a, d, rows, lane, bh, dst_tok);
+        if (d.bk == 2) pack_keys_wave<G, 2, false>(a, d, rows, none, lane, bh, dst_tok);
+        else pack_keys_wave<G, 1, false>(a, d, rows, none, lane, bh, dst_tok);
     } else {
-        if (d.bv == 2) pack_values_wave<G, 2>(a, d, rows, lane, bh, dst_tok, s_par);
-        else pack_values_wave<G, 1>(a, d, rows, lane, bh, dst_tok, s_par);
+        if (d.bv == 2) pack_values_wave<G, 2, false>(a, d, rows, none, lane, bh, dst_tok, s_par, s_par2);
+        else pack_values_wave<G, 1, false>(a, d, rows, none, lane, bh, dst_tok, s_par, s_par2);
     }
 }
 
@@ -593,8 +675,8 @@ hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipSt
     dim3 wgrid(2 * a.n_groups, a.batch * a.n_kv_heads, n_layers), wblock(64);
     if (D == 128 && g == 32 && !a.merge) xq_pack_wave_kernel<32><<<wgrid, wblock, 0, s>>>(a);
     else if (D == 128 && g == 64 && !a.merge) xq_pack_wave_kernel<64><<<wgrid, wblock, 0, s>>>(a);
-    else if (D == 128 && g == 32) xq_pack_kernel<128, 32><<<grid, block, 0, s>>>(a);  // code merging: general kernel
-    else if (D == 128 && g == 64) xq_pack_kernel<128, 64><<<grid, block, 0, s>>>(a);
+    else if (D == 128 && g == 32) xq_pack_wave_kernel<32, true><<<wgrid, wblock, 0, s>>>(a);
+    else if (D == 128 && g == 64) xq_pack_wave_kernel<64, true><<<wgrid, wblock, 0, s>>>(a);
     else if (D == 64 && g == 32) xq_pack_kernel<64, 32><<<grid, block, 0, s>>>(a);
     else if (D == 64 && g == 64) xq_pack_kernel<64, 64><<<grid, block, 0, s>>>(a);
     else return hipErrorInvalidValue;
