@@ -488,3 +488,30 @@ def test_pack_random_bit_patterns(lib_, D, g, bits):
             tl.check_stored(cache, w, st, bi, h)
             tl.check_unpack(cache, w, st, bi, h)
     cache.close()
+
+
+@pytest.mark.parametrize("D,g,R,T0,n_app", [(128, 32, 1024, 1500, 40), (64, 64, 1024, 1030, 70), (128, 64, 1024, 900, 130)])
+def test_largest_ring(lib_, D, g, R, T0, n_app):
+    """The longest fp16 window the configuration check admits (R = 1024): prompts below and above
+    it, appends that fill it and flush it."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[1 if D == 128 else 0], n_layers=2, batch=2, n_q_heads=4, n_kv_heads=2,
+                     head_dim=D, group=g, residual=R, kq=2, vq=0, km=0, vm=0, eta1=1 / 6, eta2=0.045, seed=R + D)
+    T = T0 + n_app
+    K, V = synth.kv_all(w, T)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    for t in range(T0, T):
+        cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
+    q = synth.queries(w).cuda()
+    sigma = 1.0 / np.sqrt(D)
+    outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1)]
+    for bi in range(w.batch):
+        for h in range(w.n_kv_heads):
+            st = tl.oracle_slice(w, K, V, bi, h)
+            tl.check_stored(cache, w, st, bi, h)
+            ref = tl.oracle_attention(w, st, q, bi, h, sigma)
+            for o in outs:
+                tl.check_attention(o, w, ref, bi, h)
+    cache.close()
