@@ -515,3 +515,47 @@ def test_largest_ring(lib_, D, g, R, T0, n_app):
             for o in outs:
                 tl.check_attention(o, w, ref, bi, h)
     cache.close()
+
+
+def test_maximum_counts(lib_):
+    """The largest counts the configuration check admits: 65535 (sequence, kv head) slices,
+    256 layers, 16 query heads per kv head; small tensors, sampled slices."""
+    tl = lib_
+    from paper_2510_11236_amd import XqError, cache_bytes
+    from paper_2510_11236_amd.binding import config_from_workload
+    base = synth.workloads()[0]
+    # 255 x 257 = 65535 slices, one layer, T = 70 (one packed group + ring)
+    w = synth.scaled(base, n_layers=1, batch=255, n_q_heads=257, n_kv_heads=257, seed=65)
+    T = 70
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    Kd = torch.randn((1, 255, 257, T, 64), generator=gen, device="cuda", dtype=torch.float32).half()
+    Vd = torch.randn((1, 255, 257, T, 64), generator=gen, device="cuda", dtype=torch.float32).half()
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(Kd, Vd)
+    q = torch.randn((1, 255, 257, 64), generator=gen, device="cuda", dtype=torch.float32).half()
+    out = cache.decode_attention(q, 0.125)
+    torch.cuda.synchronize()
+    for bi, h in [(0, 0), (254, 256), (100, 3), (7, 200)]:
+        K1, V1 = Kd[:, bi:bi + 1, h:h + 1].cpu(), Vd[:, bi:bi + 1, h:h + 1].cpu()
+        st = tl.oracle_slice(w, K1, V1, 0, 0)
+        # the slice sits at (bi, h) in the cache; compare its regions by hand
+        bh = bi * 257 + h
+        for pre in ("k", "v"):
+            meta = cache.region(0, pre + "_meta")[bh].cpu().numpy().view(np.uint32)
+            exp = st[0][pre + "_scale"].astype(np.uint32).reshape(-1) | (st[0][pre + "_zero"].astype(np.uint32).reshape(-1) << 16)
+            assert np.array_equal(meta[:exp.size], exp), (bi, h, pre)
+        ref = tl.oracle_attention(w, st, q[:, bi:bi + 1, h:h + 1].cpu(), 0, 0, 0.125)
+        err = float(np.max(np.abs(out[0, bi, h].cpu().numpy() - ref[0][0])))
+        assert err <= tl.ATOL, (bi, h, err)
+    cache.close()
+    with pytest.raises(XqError) as e:
+        cache_bytes(config_from_workload(synth.scaled(w, batch=256), max_tokens=T))
+    assert e.value.code == -2
+    # 256 layers in one call, pairs shared, pair-fused and sequential
+    w = synth.scaled(base, n_layers=256, batch=1, n_q_heads=1, n_kv_heads=1, kq=256, vq=128, seed=66)
+    worst = _run_prefill_case(tl, w, 100)
+    # 16 query heads per kv head
+    w = synth.scaled(synth.workloads()[1], n_layers=2, batch=1, n_q_heads=32, n_kv_heads=2, km=0, vm=0, eta1=1 / 6,
+                     eta2=0.045, seed=67)
+    worst = max(worst, _run_prefill_case(tl, w, 400))
+    print("maximum counts worst attention error", worst)
