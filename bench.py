@@ -145,7 +145,7 @@ def main():
     stride = next(s for s in (37, 41, 43, 47, 53, 1) if np.gcd(s, nbh) == 1)
     sample = [divmod((3 + stride * i) % nbh, w.n_kv_heads) for i in range(min(args.cpu_slices, nbh))]
     slices = {}
-    pack_ms, pack_bytes = 0.0, 0
+    pack_ms, pack_bytes, pack_written = 0.0, 0, 0
     pend = []
     for l, K, V in synth.kv_layers(w, Ttot, dev):
         new_k[:, l] = K[:, :, T0:].permute(2, 0, 1, 3)
@@ -169,6 +169,13 @@ def main():
             torch.cuda.synchronize()
             pack_ms += e0.elapsed_time(e1)
             pack_bytes += Kp.numel() * 2 * 2
+            for ll in range(l + 1 - len(pend), l + 1):     # bytes the pack writes: codes (storing layers) + metadata
+                for is_v in (False, True):
+                    bits = 2 if ll < (w.vq if is_v else w.kq) else 1
+                    stores = ll < (w.vm if is_v else w.km) or ll % 2 == 0
+                    tq = 0 if T0 <= w.residual else w.group * ((T0 - w.residual + w.group - 1) // w.group)
+                    elems = w.batch * w.n_kv_heads * tq * w.head_dim
+                    pack_written += elems * (bits if stores else 0) // 8 + elems * 4 // w.group
             del Kp, Vp
             pend = []
     del K, V
@@ -269,6 +276,10 @@ def main():
         "decode_one_call_per_layer_ms": per_layer_ms,
         "append_ms": ms_per_step - decode_ms,
         "pack_GBps_fp16_read": pack_bytes / (pack_ms * 1e-3) / 1e9,
+        "pack_roofline": {"bound": "hbm", "kernel": "xq_pack_wave_kernel" if w.head_dim == 128 else "xq_pack_kernel",
+                          "achieved": (pack_bytes + pack_written) / (pack_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                          "unit": "GB/s", "frac": (pack_bytes + pack_written) / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          "bytes_read": pack_bytes, "bytes_written": pack_written},
         "equivalent_bits": {"paper_definition": equivalent_bits(cfg), "with_metadata_and_ring": equivalent_bits(cfg, True, T0)},
     }
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
