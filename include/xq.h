@@ -63,6 +63,9 @@
  *   V meta   [token t][channel group d/g] of 4 bytes, same halves.
  *   residual [slot t mod R][D] fp16, for K and for V.
  * Only layers that store codes have code regions.
+ * In a paged cache the regions are [page][kv head] instead of [batch][kv head], a region's
+ * per-slice size is that of one page, token t of a sequence is token t mod page_tokens of the
+ * sequence's page number t / page_tokens, and the layouts above apply inside a page.
  */
 #ifndef XQ_H
 #define XQ_H
@@ -104,6 +107,12 @@ typedef struct xq_config {
     int32_t share_dominant;  /* k in [0, G): the layer of each group whose codes are stored */
     int32_t merge_mode;      /* XQ_MERGE_*: how the stored codes of a pair are formed (G = 2, k = 0 only) */
     float gamma0;            /* weight of the first layer's codes for XQ_MERGE_ROUND, in [0, 1] */
+    /* Paged cache (both zero = every sequence owns room for max_tokens).  The packed tokens of a
+     * sequence live in pages of page_tokens tokens taken from a pool of n_pages that all
+     * sequences share; a page spans every layer and kv head.  max_tokens stays the limit per
+     * sequence.  The fp16 rings are per sequence and not paged. */
+    int32_t page_tokens;     /* 0, or a power of two >= 128 */
+    int32_t n_pages;         /* pool size when page_tokens != 0 */
 } xq_config;
 
 /* merge_mode: stored codes e_m of a sharing pair from the two layers' own codes e_0, e_1 */
@@ -194,8 +203,17 @@ int xq_code_delta_histogram(const xq_cache *cache, int32_t layer, int32_t is_v, 
 
 /* Byte offsets of a layer's regions inside the arena (host pointer to 6 values:
  * k_codes, v_codes, k_meta, v_meta, k_residual, v_residual; a code offset is -1 for a layer
- * that stores none) and, in sizes[6], the bytes of each region per (batch, kv head). */
+ * that stores none) and, in sizes[6], the bytes of each region per (batch, kv head) -- per
+ * (page, kv head) for the four packed regions of a paged cache. */
 int xq_cache_layout(const xq_cache *cache, int32_t layer, int64_t offsets[6], int64_t sizes[6]);
+
+/* Paged caches: the pages sequence seq holds, in token order (host pointers; at most cap values
+ * are written to pages, *n receives the count) and the number of free pages in the pool.
+ * Pages are taken when a prefill or a ring flush needs them (XQ_ERR_CAPACITY when the pool is
+ * empty; nothing is enqueued then) and go back to the pool with xq_cache_reset /
+ * xq_cache_reset_seq.  XQ_ERR_STATE on a cache that is not paged. */
+int xq_cache_pages(const xq_cache *cache, int32_t seq, int32_t *pages, int32_t cap, int32_t *n);
+int xq_cache_free_pages(const xq_cache *cache, int32_t *n_free);
 
 /* Test/tuning hook: forces the number of 128-token tiles per packed-token split used by
  * xq_decode_attention (0 restores the automatic plan).  Results must not depend on it beyond

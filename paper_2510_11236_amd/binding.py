@@ -28,7 +28,7 @@ class XqConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "group",
                                          "residual", "max_tokens", "kq", "vq", "km", "vm")] + \
                [("eta1", C.c_float), ("eta2", C.c_float), ("share_group", C.c_int32), ("share_dominant", C.c_int32),
-                ("merge_mode", C.c_int32), ("gamma0", C.c_float)]
+                ("merge_mode", C.c_int32), ("gamma0", C.c_float), ("page_tokens", C.c_int32), ("n_pages", C.c_int32)]
 
 
 def lib():
@@ -52,6 +52,8 @@ def lib():
                                            C.c_int32, vp]
         L.xq_cache_len_seq.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.xq_cache_reset_seq.argtypes = [vp, C.c_int32]
+        L.xq_cache_pages.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
+        L.xq_cache_free_pages.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xq_append_token.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         L.xq_decode_attention.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, vp, C.c_size_t, C.c_int32, vp]
         L.xq_unpack_codes.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
@@ -131,12 +133,42 @@ class XqCache:
         return {n: (int(off[i]), int(sz[i])) for i, n in enumerate(names)}
 
     def region(self, layer, name):
-        """uint8 view [batch*kv_heads][bytes] of one region of a layer (for tests)."""
+        """uint8 view [slices][bytes] of one region of a layer (for tests): one slice per
+        (sequence, kv head), or per (page, kv head) for the packed regions of a paged cache."""
         off, sz = self.layout(layer)[name]
         if off < 0:
             return None
-        nbh = self.cfg.batch * self.cfg.n_kv_heads
-        return self.arena[off:off + nbh * sz].view(nbh, sz)
+        n = self.cfg.batch * self.cfg.n_kv_heads
+        if self.cfg.page_tokens and not name.endswith("_res"):
+            n = self.cfg.n_pages * self.cfg.n_kv_heads
+        return self.arena[off:off + n * sz].view(n, sz)
+
+    def pages(self, seq):
+        """Pages held by a sequence of a paged cache, in token order."""
+        n = C.c_int32(0)
+        _check(lib().xq_cache_pages(self._h, seq, None, 0, C.byref(n)), "xq_cache_pages")
+        buf = (C.c_int32 * max(n.value, 1))()
+        _check(lib().xq_cache_pages(self._h, seq, buf, n.value, C.byref(n)), "xq_cache_pages")
+        return list(buf[:n.value])
+
+    def free_pages(self):
+        n = C.c_int32(0)
+        _check(lib().xq_cache_free_pages(self._h, C.byref(n)), "xq_cache_free_pages")
+        return n.value
+
+    def slice_bytes(self, layer, name, bh):
+        """The bytes one (sequence, kv head) holds in a region, in token order (for tests): a row of
+        region(), or the sequence's pages one after the other."""
+        r = self.region(layer, name)
+        if r is None:
+            return None
+        if not self.cfg.page_tokens or name.endswith("_res"):
+            return r[bh]
+        bi, h = divmod(bh, self.cfg.n_kv_heads)
+        rows = [p * self.cfg.n_kv_heads + h for p in self.pages(bi)]
+        if not rows:
+            return r[0][:0]
+        return r[torch.tensor(rows, device=r.device)].reshape(-1)
 
     def quantize_pack(self, k: torch.Tensor, v: torch.Tensor, layer0=0):
         """k, v: fp16 [n_layers][b][h_kv][T][D] (any strides with contiguous D)."""
@@ -193,8 +225,9 @@ class XqCache:
         lib().xq_debug_set_tiles_per_split(self._h, int(n))
 
 
-def config_from_workload(w, max_tokens=None) -> XqConfig:
+def config_from_workload(w, max_tokens=None, page_tokens=0, n_pages=0) -> XqConfig:
     """XqConfig for a synth.Workload (marshalling helper)."""
     mt = max_tokens if max_tokens is not None else w.context + w.decode_steps
     return XqConfig(w.n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.group, w.residual, mt,
-                    w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.share_group, w.share_dominant, w.merge_mode, w.gamma0)
+                    w.kq, w.vq, w.km, w.vm, w.eta1, w.eta2, w.share_group, w.share_dominant, w.merge_mode, w.gamma0,
+                    page_tokens, n_pages)

@@ -140,7 +140,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     PartT *s_part = (PartT *)s_raw;
     QT &s_q = *(QT *)(s_raw + KP_BYTES + 4 * sizeof(VwT));
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // the wave index as a scalar: everything derived from the tile number then lives in SGPRs
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     // 1-D grid, XCD-aware: workgroups go round-robin over the 8 XCDs by linear id, so the
     // (equal-sized) packed-token workgroups come first and the small ring workgroups last;
     // interleaving the two kinds would hand some XCDs only ring work.
@@ -222,6 +223,10 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             const int tile = tile0 + (it + rot) % n_tiles;
             const int blk = tile * 4 + row;
             const bool row_ok = blk < n_blocks;
+            // where the tile's 128 tokens are stored: the sequence's own slice, or a page's
+            int tin;
+            const int64_t slice = xq_locate(a.pg, bi, hkv, a.n_kv_heads, tile * XQ_TILE_TOKENS, &tin);
+            const int blk_in = tin / 32 + row;
             // ---- key weights for the tile's groups -> LDS
             float zs[NV];
             {
@@ -230,8 +235,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 uint32_t meta[NLAY][CPP];
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y) {
-                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + (int64_t)bh * a.st.k_meta) +
-                                         (int64_t)Gidx * D + li * CPP;
+                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + slice * a.st.k_meta) +
+                                         (int64_t)(tin / G + gi) * D + li * CPP;
                     if (g_ok) VecLoad<CPP>::ld(mp, meta[y]);
                     else {
 #pragma unroll
@@ -278,8 +283,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             uint32_t kc[2][WK];
             {
                 const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
-                                                        (int64_t)bh * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
-                                     (int64_t)blk * 32 * WK;
+                                                        slice * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
+                                     (int64_t)blk_in * 32 * WK;
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -301,11 +306,11 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             auto load_values = [&]() {
                 {
                     const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
-                                                            (int64_t)bh * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
+                                                            slice * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
                     for (int kb = 0; kb < 4; ++kb) {
                         const int b2 = tile * 4 + kb;
-                        if (b2 < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)b2 * 64 * WS + lane * WS, vc[kb]);
+                        if (b2 < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)(tin / 32 + kb) * 64 * WS + lane * WS, vc[kb]);
                         else {
 #pragma unroll
                             for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
@@ -316,8 +321,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 for (int y = 0; y < NLAY; ++y)
 #pragma unroll
                     for (int s = 0; s < 2; ++s) {
-                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + (int64_t)bh * a.st.v_meta) +
-                                             ((int64_t)blk * 32 + r16 + 16 * s) * NJ;
+                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + slice * a.st.v_meta) +
+                                             ((int64_t)blk_in * 32 + r16 + 16 * s) * NJ;
                         if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
                         else {
 #pragma unroll

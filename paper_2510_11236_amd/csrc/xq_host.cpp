@@ -74,6 +74,13 @@ int check_config(const xq_config *c) {
     if (c->merge_mode < XQ_MERGE_NONE || c->merge_mode > XQ_MERGE_CEIL) return XQ_ERR_INVALID_ARG;
     if (c->merge_mode != XQ_MERGE_NONE && (G != 2 || c->share_dominant != 0)) return XQ_ERR_INVALID_ARG;
     if (c->merge_mode == XQ_MERGE_ROUND && !(c->gamma0 >= 0.0f && c->gamma0 <= 1.0f)) return XQ_ERR_INVALID_ARG;
+    if (c->page_tokens != 0) {
+        if (c->page_tokens < XQ_TILE_TOKENS || (c->page_tokens & (c->page_tokens - 1)) || c->n_pages < 1)
+            return XQ_ERR_INVALID_ARG;
+        if ((int64_t)c->n_pages * c->n_kv_heads > INT32_MAX) return XQ_ERR_UNSUPPORTED;
+    } else if (c->n_pages != 0) {
+        return XQ_ERR_INVALID_ARG;
+    }
     // the layers that share one code tensor must have one bit width
     for (int l = 0; l < c->n_layers; ++l) {
         if (bits_of(*c, l, false) != bits_of(*c, code_layer(*c, l, false), false)) return XQ_ERR_INVALID_ARG;
@@ -85,6 +92,8 @@ int check_config(const xq_config *c) {
 struct Carve {
     XqStrides st;
     int64_t total;
+    int64_t page_table;  // byte offset of the device page table (paged caches)
+    int32_t max_pages;   // its width: pages a sequence can hold
 };
 
 // Lays the regions out; fills descs when not null.
@@ -92,15 +101,21 @@ Carve carve(const xq_config &c, XqLayerDesc *descs) {
     Carve r;
     const int64_t D = c.head_dim, g = c.group, R = c.residual;
     const int64_t maxTq = xq_quantized_len(c.max_tokens, c.group, c.residual);
-    const int64_t nbh = (int64_t)c.batch * c.n_kv_heads;
-    r.st.k_codes2 = maxTq * D * 2 / 8;
-    r.st.k_codes1 = maxTq * D * 1 / 8;
+    const int64_t nbh = (int64_t)c.batch * c.n_kv_heads;  // ring slices
+    const bool paged = c.page_tokens != 0;
+    const int64_t cap = paged ? c.page_tokens : maxTq;     // tokens per packed slice
+    const int64_t nsl = paged ? (int64_t)c.n_pages * c.n_kv_heads : nbh;  // packed slices
+    r.st.k_codes2 = cap * D * 2 / 8;
+    r.st.k_codes1 = cap * D * 1 / 8;
     r.st.v_codes2 = r.st.k_codes2;
     r.st.v_codes1 = r.st.k_codes1;
-    r.st.k_meta = (maxTq / g) * D * 4;
-    r.st.v_meta = maxTq * (D / g) * 4;
+    r.st.k_meta = (cap / g) * D * 4;
+    r.st.v_meta = cap * (D / g) * 4;
     r.st.res = R * D * 2;
     int64_t off = align256((int64_t)sizeof(XqLayerDesc) * c.n_layers);
+    r.max_pages = paged ? (int32_t)((maxTq + c.page_tokens - 1) / c.page_tokens) : 0;
+    r.page_table = off;
+    if (paged) off = align256(off + (int64_t)c.batch * (r.max_pages > 0 ? r.max_pages : 1) * 4);
     for (int l = 0; l < c.n_layers; ++l) {
         XqLayerDesc d;
         d.bk = bits_of(c, l, false);
@@ -112,16 +127,16 @@ Carve carve(const xq_config &c, XqLayerDesc *descs) {
         d.k_codes = d.v_codes = 0;  // a sharing layer's are filled in below
         if (d.k_store) {
             d.k_codes = off;
-            off = align256(off + nbh * (d.bk == 2 ? r.st.k_codes2 : r.st.k_codes1));
+            off = align256(off + nsl * (d.bk == 2 ? r.st.k_codes2 : r.st.k_codes1));
         }
         if (d.v_store) {
             d.v_codes = off;
-            off = align256(off + nbh * (d.bv == 2 ? r.st.v_codes2 : r.st.v_codes1));
+            off = align256(off + nsl * (d.bv == 2 ? r.st.v_codes2 : r.st.v_codes1));
         }
         d.k_meta = off;
-        off = align256(off + nbh * r.st.k_meta);
+        off = align256(off + nsl * r.st.k_meta);
         d.v_meta = off;
-        off = align256(off + nbh * r.st.v_meta);
+        off = align256(off + nsl * r.st.v_meta);
         d.k_res = off;
         off = align256(off + nbh * r.st.res);
         d.v_res = off;
@@ -233,6 +248,16 @@ int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, x
     c->arena = (char *)dev_arena;
     c->arena_bytes = arena_bytes;
     c->dev_layers = (XqLayerDesc *)dev_arena;
+    c->paging.table = nullptr;
+    c->paging.shift = 0;
+    c->paging.max_pages = cv.max_pages;
+    if (cfg->page_tokens != 0) {
+        c->paging.table = (const int32_t *)(c->arena + cv.page_table);
+        while ((1 << c->paging.shift) < cfg->page_tokens) ++c->paging.shift;
+        c->page_table.assign((size_t)cfg->batch * cv.max_pages, -1);
+        c->pages_used.assign(cfg->batch, 0);
+        for (int p = cfg->n_pages - 1; p >= 0; --p) c->free_pages.push_back(p);  // page 0 is handed out first
+    }
     if (hipMemcpy(c->dev_layers, c->layers, sizeof(XqLayerDesc) * cfg->n_layers, hipMemcpyHostToDevice) != hipSuccess) {
         delete c;
         return XQ_ERR_HIP;
@@ -256,15 +281,73 @@ static bool rows_equal(const xq_cache *c, int l0, int l1) {
     return memcmp(len_row(c, l0), len_row(c, l1), sizeof(int32_t) * c->cfg.batch) == 0;
 }
 
+// ---- paged caches: pages are handed out in the order sequences need them
+static void release_pages(xq_cache *c, int seq) {
+    int32_t *row = c->page_table.data() + (size_t)seq * c->paging.max_pages;
+    for (int k = c->pages_used[seq] - 1; k >= 0; --k) {
+        c->free_pages.push_back(row[k]);
+        row[k] = -1;
+    }
+    c->pages_used[seq] = 0;
+}
+static int pages_for(const xq_cache *c, int Tq) { return (Tq + c->cfg.page_tokens - 1) >> c->paging.shift; }
+// Pages that sequences seq0 .. seq0 + n_seq - 1 still lack for new_Tq[i] packed tokens each.
+static int64_t pages_missing(const xq_cache *c, int seq0, int n_seq, const int32_t *new_Tq) {
+    int64_t need = 0;
+    for (int i = 0; i < n_seq; ++i) need += std::max(0, pages_for(c, new_Tq[i]) - c->pages_used[seq0 + i]);
+    return need;
+}
+// Takes the missing pages (the caller has checked that the pool holds them) and enqueues the
+// device table updates on the stream, ahead of the kernels that will use them.
+static int take_pages(xq_cache *c, int seq0, int n_seq, const int32_t *new_Tq, hipStream_t s) {
+    XqPageUpdateArgs u;
+    u.table = const_cast<int32_t *>(c->paging.table);
+    u.n = 0;
+    for (int i = 0; i < n_seq; ++i) {
+        const int seq = seq0 + i, want = pages_for(c, new_Tq[i]);
+        int32_t *row = c->page_table.data() + (size_t)seq * c->paging.max_pages;
+        while (c->pages_used[seq] < want) {
+            const int slot = c->pages_used[seq]++;
+            row[slot] = c->free_pages.back();
+            c->free_pages.pop_back();
+            u.index[u.n] = seq * c->paging.max_pages + slot;
+            u.page[u.n] = row[slot];
+            if (++u.n == XQ_PAGE_UPDATES) {
+                if (xq_launch_page_update(u, s) != hipSuccess) return XQ_ERR_HIP;
+                u.n = 0;
+            }
+        }
+    }
+    return xq_launch_page_update(u, s) == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+int xq_cache_pages(const xq_cache *cache, int32_t seq, int32_t *pages, int32_t cap, int32_t *n) {
+    if (!cache || seq < 0 || seq >= cache->cfg.batch || cap < 0 || (cap > 0 && !pages)) return XQ_ERR_INVALID_ARG;
+    if (!cache->paging.table) return XQ_ERR_STATE;
+    const int used = cache->pages_used[seq];
+    for (int k = 0; k < used && k < cap; ++k) pages[k] = cache->page_table[(size_t)seq * cache->paging.max_pages + k];
+    if (n) *n = used;
+    return XQ_OK;
+}
+
+int xq_cache_free_pages(const xq_cache *cache, int32_t *n_free) {
+    if (!cache || !n_free) return XQ_ERR_INVALID_ARG;
+    if (!cache->paging.table) return XQ_ERR_STATE;
+    *n_free = (int32_t)cache->free_pages.size();
+    return XQ_OK;
+}
+
 int xq_cache_reset(xq_cache *cache) {
     if (!cache) return XQ_ERR_INVALID_ARG;
     std::fill(cache->len.begin(), cache->len.end(), 0);
+    for (int i = 0; i < cache->cfg.batch && cache->paging.table; ++i) release_pages(cache, i);
     return XQ_OK;
 }
 
 int xq_cache_reset_seq(xq_cache *cache, int32_t seq) {
     if (!cache || seq < 0 || seq >= cache->cfg.batch) return XQ_ERR_INVALID_ARG;
     for (int l = 0; l < cache->cfg.n_layers; ++l) len_row(cache, l)[seq] = 0;
+    if (cache->paging.table) release_pages(cache, seq);
     return XQ_OK;
 }
 
@@ -343,6 +426,12 @@ int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int3
             if (len_row(cache, l)[i] != 0) return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
     const int Tq = xq_quantized_len(T, c.group, c.residual);
+    if (cache->paging.table && Tq > 0) {
+        std::vector<int32_t> want(n_seq, Tq);
+        if (pages_missing(cache, seq0, n_seq, want.data()) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
+        int rc = take_pages(cache, seq0, n_seq, want.data(), s);
+        if (rc) return rc;
+    }
     if (Tq > 0) {
         XqPackArgs a;
         memset(&a, 0, sizeof(a));
@@ -363,6 +452,7 @@ int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int3
         a.from_ring = 0;
         a.src_tok0 = 0;
         a.dst_tok0 = 0;
+        a.pg = cache->paging;
         a.n_groups = Tq / c.group;
         fill_pack_consts(c, a);
         if (xq_launch_pack(a, c.head_dim, c.group, n_layers, s) != hipSuccess) return XQ_ERR_HIP;
@@ -415,6 +505,17 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
             if ((merges_next(c, l, false) || merges_next(c, l, true)) && !rows_equal(cache, l, l + 1))
                 return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (cache->paging.table) {  // pages for the groups that this call's ring flushes will write
+        std::vector<int32_t> want(c.batch, 0);
+        for (int l = layer0; l < layer0 + n_layers; ++l)
+            for (int i = 0; i < c.batch; ++i) {
+                const int t = len_row(cache, l)[i], tq = xq_quantized_len(t, c.group, c.residual);
+                want[i] = std::max(want[i], t - tq == c.residual ? tq + c.group : tq);
+            }
+        if (pages_missing(cache, 0, c.batch, want.data()) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
+        int rc = take_pages(cache, 0, c.batch, want.data(), s);
+        if (rc) return rc;
+    }
     const int64_t D = c.head_dim;
     const int64_t per_layer = (int64_t)c.batch * c.n_kv_heads * D;
     // runs of consecutive layers with the same lengths share their launches
@@ -442,6 +543,7 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
             a.src_tok0 = Tq % c.residual;
             a.dst_tok0 = Tq;
             a.n_groups = 1;
+            a.pg = cache->paging;
             a.ragged = ragged;
             if (ragged) memcpy(a.seq_T, row, sizeof(int32_t) * c.batch);
             fill_pack_consts(c, a);
@@ -556,6 +658,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.out = (float *)out_f32 + (int64_t)(l - layer0) * per_layer_q;
         a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
+        a.pg = cache->paging;
         if (!fused)
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;
@@ -586,6 +689,8 @@ int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t 
     a.stride = is_v ? (a.B == 2 ? cache->strides.v_codes2 : cache->strides.v_codes1)
                     : (a.B == 2 ? cache->strides.k_codes2 : cache->strides.k_codes1);
     a.n_bh = c.batch * c.n_kv_heads;
+    a.n_kv_heads = c.n_kv_heads;
+    a.pg = cache->paging;
     a.Tq = Tq;
     a.D = c.head_dim;
     a.is_v = is_v ? 1 : 0;
@@ -610,6 +715,7 @@ int xq_code_delta_histogram(const xq_cache *cache, int32_t layer, int32_t is_v, 
     a.stride = is_v ? (B == 2 ? cache->strides.v_codes2 : cache->strides.v_codes1)
                     : (B == 2 ? cache->strides.k_codes2 : cache->strides.k_codes1);
     a.n_kv_heads = c.n_kv_heads;
+    a.pg = cache->paging;
     a.n_bh = c.batch * c.n_kv_heads;
     a.B = B;
     a.words_per_token = c.head_dim * B / 32;

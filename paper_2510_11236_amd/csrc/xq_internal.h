@@ -10,8 +10,9 @@
 #define XQ_MAX_LAYERS 256
 #define XQ_MAX_SPLITS 64     // packed-token splits per (layer, sequence, kv head)
 #define XQ_TILE_TOKENS 128   // tokens one wave handles per iteration of the decode loop
-#define XQ_MAX_RAGGED 256
-#define XQ_MAX_REP 16  /* query heads per kv head */    // largest batch whose sequences may have different lengths
+#define XQ_MAX_RAGGED 256    // largest batch whose sequences may have different lengths
+#define XQ_MAX_REP 16        // query heads per kv head
+#define XQ_PAGE_UPDATES 240  // page-table entries one update launch carries in its arguments
 
 // Where a layer's regions live inside the arena (byte offsets) and what it holds.
 // k_codes / v_codes point at the codes the layer READS: its own, or those of the
@@ -25,12 +26,33 @@ struct XqLayerDesc {
     int32_t k_merge, v_merge;  // 1 if its stored codes are merged with those of the next layer
 };
 
-// Per (batch, kv head) strides in bytes; identical for every layer.
+// Per slice strides in bytes; identical for every layer.  A slice is one (sequence, kv head)
+// with room for max_tokens, or, in a paged cache, one (page, kv head) with room for a page.
 struct XqStrides {
     int64_t k_codes2, k_codes1;  // key codes at 2 / 1 bit
     int64_t v_codes2, v_codes1;
     int64_t k_meta, v_meta, res;
 };
+
+// Where the packed tokens of a sequence live.  Contiguous cache: table == nullptr, sequence i
+// owns slice row i.  Paged cache: token t of sequence i is token t mod P of page
+// table[i * max_pages + t / P], P = 1 << shift tokens (a multiple of the 128-token decode tile).
+// The fp16 rings are never paged.
+struct XqPaging {
+    const int32_t *table;
+    int32_t shift, max_pages;
+};
+// Slice index (row of a [slice][bytes] region) that holds packed token tok of (sequence, kv head);
+// *tok_in = index of the token inside the slice.
+__host__ __device__ static inline int64_t xq_locate(const XqPaging &p, int seq, int hkv, int n_kv_heads, int tok,
+                                                    int *tok_in) {
+    if (!p.table) {
+        *tok_in = tok;
+        return (int64_t)seq * n_kv_heads + hkv;
+    }
+    *tok_in = tok & ((1 << p.shift) - 1);
+    return (int64_t)p.table[(int64_t)seq * p.max_pages + (tok >> p.shift)] * n_kv_heads + hkv;
+}
 
 struct xq_cache {
     xq_config cfg;
@@ -40,6 +62,10 @@ struct xq_cache {
     XqLayerDesc *dev_layers;  // copy at the start of the arena
     XqStrides strides;
     std::vector<int32_t> len;  // tokens held, [layer][sequence]
+    // paged cache: host mirror of the page table ([sequence][max_pages], -1 = none), pages in
+    // use per sequence, free pages (a stack), device table inside the arena
+    XqPaging paging;           // table == nullptr for a contiguous cache
+    std::vector<int32_t> page_table, pages_used, free_pages;
     int32_t tiles_per_split_override;  // 0 = automatic
 };
 
@@ -71,6 +97,7 @@ struct XqPackArgs {
     // ring flush of a batch with per-sequence lengths: sequence i holds seq_T[i] tokens and is
     // flushed (its oldest g ring tokens) only if its ring is full; src/dst offsets follow from it
     int32_t ragged;
+    XqPaging pg;
     int32_t seq_T[XQ_MAX_RAGGED];
 };
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s);
@@ -108,6 +135,7 @@ struct XqDecodeArgs {
     int32_t group;       // g, for the split rule
     int32_t rep, q_head0;  // query heads per kv head; first of them that this launch serves (it serves n_rep)
     int32_t reuse_codes;  // some layer of the launch reads another layer's codes (keep them in L2)
+    XqPaging pg;
     int32_t seq_T[XQ_MAX_RAGGED];
 };
 // bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs;
@@ -121,15 +149,17 @@ bool xq_decode_can_fuse(int D, int g, int n_rep);
 
 struct XqUnpackArgs {
     const char *codes;  // region of the layer that stores them
-    int64_t stride;     // per (batch, kv head), bytes
-    int32_t n_bh, Tq, D, B, is_v;
+    int64_t stride;     // per slice, bytes
+    int32_t n_bh, n_kv_heads, Tq, D, B, is_v;
+    XqPaging pg;
     uint8_t *out;
 };
 hipError_t xq_launch_unpack(const XqUnpackArgs &a, hipStream_t s);
 
 struct XqDeltaArgs {
     const char *codes_a, *codes_b;  // code regions of the two layers
-    int64_t stride;                 // per (batch, kv head), bytes
+    int64_t stride;                 // per slice, bytes
+    XqPaging pg;
     int32_t n_kv_heads, n_bh, B;
     int32_t words_per_token;        // D * B / 32
     int32_t ragged, Tq;             // packed tokens, or per sequence from seq_Tq
@@ -137,3 +167,11 @@ struct XqDeltaArgs {
     unsigned long long *counts;     // 4 values
 };
 hipError_t xq_launch_delta_histogram(const XqDeltaArgs &a, hipStream_t s);
+
+// Writes n (index, page) pairs into the device page table (paged caches).
+struct XqPageUpdateArgs {
+    int32_t *table;
+    int32_t n;
+    int32_t index[XQ_PAGE_UPDATES], page[XQ_PAGE_UPDATES];
+};
+hipError_t xq_launch_page_update(const XqPageUpdateArgs &a, hipStream_t s);

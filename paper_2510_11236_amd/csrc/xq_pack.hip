@@ -70,7 +70,9 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
         src_tok0 = Tq % a.R;
         dst_tok0 = Tq;
     }
-    const int dst_tok = dst_tok0 + grp * G;
+    // destination inside the slice that holds the group (the sequence's own, or a page's)
+    int dst_tok;
+    const int64_t slice = xq_locate(a.pg, bh / a.n_kv_heads, bh % a.n_kv_heads, a.n_kv_heads, dst_tok0 + grp * G, &dst_tok);
 
     auto half_at = [&](int t, int c) -> float {
         uint32_t w = tile[t * LDW + (c >> 1)];
@@ -159,9 +161,9 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
             s_sc[tid] = s;
             uint32_t *mp;
             if (!is_v)
-                mp = (uint32_t *)(a.arena + d.k_meta + (int64_t)bh * a.st.k_meta) + (int64_t)(dst_tok / G) * D + tid;
+                mp = (uint32_t *)(a.arena + d.k_meta + slice * a.st.k_meta) + (int64_t)(dst_tok / G) * D + tid;
             else
-                mp = (uint32_t *)(a.arena + d.v_meta + (int64_t)bh * a.st.v_meta) + (int64_t)dst_tok * NJ + tid;
+                mp = (uint32_t *)(a.arena + d.v_meta + slice * a.st.v_meta) + (int64_t)dst_tok * NJ + tid;
             *mp = meta;
             if (mg) {  // the next layer's own scale for its own codes (its metadata is written by its workgroup)
                 float mn2, mx2;
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
             if (!is_v) {
                 const int W = D / per, CW = W < 4 ? W : 4;
                 const int64_t cs = B == 2 ? a.st.k_codes2 : a.st.k_codes1;
-                uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + (int64_t)bh * cs);
+                uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + slice * cs);
                 for (int idx = tid; idx < G * W; idx += 256) {
                     int sb = idx / (32 * W), ib = idx % (32 * W);
                     int chunk = ib / (32 * CW), tau = (ib / CW) % 32, wc = ib % CW;
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(256) void xq_pack_kernel(XqPackArgs a) {
             } else {
                 const int WS = CPL * B;
                 const int64_t cs = B == 2 ? a.st.v_codes2 : a.st.v_codes1;
-                uint32_t *cp = (uint32_t *)(a.arena + d.v_codes + (int64_t)bh * cs);
+                uint32_t *cp = (uint32_t *)(a.arena + d.v_codes + slice * cs);
                 for (int idx = tid; idx < (G / 32) * 64 * WS; idx += 256) {
                     int sb = idx / (64 * WS), ib = idx % (64 * WS);
                     int slot = ib / WS, m = ib % WS;
@@ -350,7 +352,7 @@ __device__ __forceinline__ uint32_t dpp_or(uint32_t x) {
 // MG: the stored codes are merged with the next layer's own codes, whose rows are rows2.
 template <int G, int B, bool MG>
 __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
-                                               const uint32_t (&rows2)[MG ? G : 1], int lane, int bh, int dst_tok) {
+                                               const uint32_t (&rows2)[MG ? G : 1], int lane, int64_t slice, int dst_tok) {
     constexpr int D = 128;
     // ---- per-channel min / max down the g tokens (two channels per lane)
     uint32_t pa = 0x7c007c00u, pb = 0x7c007c00u;  // (+inf, +inf)
@@ -363,7 +365,7 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     uint32_t ma, mb;
     const GroupQ qa = group_quant<B>(pair_min(pa), pair_max(pa), c1, c2, &ma);
     const GroupQ qb = group_quant<B>(pair_min(pb), pair_max(pb), c1, c2, &mb);
-    uint32_t *mp = (uint32_t *)(a.arena + d.k_meta + (int64_t)bh * a.st.k_meta) + (int64_t)(dst_tok / G) * D + 2 * lane;
+    uint32_t *mp = (uint32_t *)(a.arena + d.k_meta + slice * a.st.k_meta) + (int64_t)(dst_tok / G) * D + 2 * lane;
     __builtin_nontemporal_store(ma, mp);  // streamed out once: keep it out of the way of the reads
     __builtin_nontemporal_store(mb, mp + 1);
     if (!d.k_store) return;
@@ -384,7 +386,7 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     constexpr int LW = 16 / B;             // lanes per word
     constexpr int W = D * B / 32;          // words per token row
     constexpr int CW = 4;
-    uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + (int64_t)bh * (B == 2 ? a.st.k_codes2 : a.st.k_codes1));
+    uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + slice * (B == 2 ? a.st.k_codes2 : a.st.k_codes1));
     const int wsel = lane / LW, lsel = lane % LW;
     // batches of LW rows: the OR trees of a batch run side by side, so that no instruction
     // waits on the DPP read-after-write hazard of its own row
@@ -424,12 +426,12 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
 
 template <int G, int B, bool MG>
 __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
-                                                 const uint32_t (&rows2)[MG ? G : 1], int lane, int bh, int dst_tok,
+                                                 const uint32_t (&rows2)[MG ? G : 1], int lane, int64_t slice, int dst_tok,
                                                  float4 *s_par, float4 *s_par2) {
     constexpr int D = 128, NJ = D / G, LPG = G / 2;  // lanes per channel group
     const int j = lane / LPG, i = lane % LPG;
     const float c1 = B == 2 ? a.c1_2 : a.c1_1, c2 = B == 2 ? a.c2_2 : a.c2_1;
-    uint32_t *mp = (uint32_t *)(a.arena + d.v_meta + (int64_t)bh * a.st.v_meta) + (int64_t)dst_tok * NJ;
+    uint32_t *mp = (uint32_t *)(a.arena + d.v_meta + slice * a.st.v_meta) + (int64_t)dst_tok * NJ;
     // ---- per-token min / max along the g channels of a group: reduce over the LPG lanes, then
     // lane i of the group keeps token (chunk * LPG + i), so each lane owns one group's parameters
 #pragma unroll
@@ -471,7 +473,7 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
     // ---- codes: this lane's two channels over TPW tokens fill one word, highest token first
     constexpr int TPW = 16 / B;   // tokens per word
     constexpr int WS = 2 * B;     // words per 32-token block
-    uint32_t *cp = (uint32_t *)(a.arena + d.v_codes + (int64_t)bh * (B == 2 ? a.st.v_codes2 : a.st.v_codes1));
+    uint32_t *cp = (uint32_t *)(a.arena + d.v_codes + slice * (B == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
     for (int blk = 0; blk < G / 32; ++blk) {
         uint32_t words[WS];
@@ -533,7 +535,9 @@ __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
         src_tok0 = Tq % a.R;
         dst_tok0 = Tq;
     }
-    const int dst_tok = dst_tok0 + grp * G;
+    // destination inside the slice that holds the group (the sequence's own, or a page's)
+    int dst_tok;
+    const int64_t slice = xq_locate(a.pg, bh / a.n_kv_heads, bh % a.n_kv_heads, a.n_kv_heads, dst_tok0 + grp * G, &dst_tok);
     const uint16_t *src;
     int64_t s_tok;
     if (a.from_ring) {
@@ -563,21 +567,21 @@ __global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
 #pragma unroll
             for (int t = 0; t < G; ++t) rows2[t] = __builtin_nontemporal_load((const uint32_t *)(src2 + t * s_tok + 2 * lane));
             if (!is_v) {
-                if (d.bk == 2) pack_keys_wave<G, 2, true>(a, d, rows, rows2, lane, bh, dst_tok);
-                else pack_keys_wave<G, 1, true>(a, d, rows, rows2, lane, bh, dst_tok);
+                if (d.bk == 2) pack_keys_wave<G, 2, true>(a, d, rows, rows2, lane, slice, dst_tok);
+                else pack_keys_wave<G, 1, true>(a, d, rows, rows2, lane, slice, dst_tok);
             } else {
-                if (d.bv == 2) pack_values_wave<G, 2, true>(a, d, rows, rows2, lane, bh, dst_tok, s_par, s_par2);
-                else pack_values_wave<G, 1, true>(a, d, rows, rows2, lane, bh, dst_tok, s_par, s_par2);
+                if (d.bv == 2) pack_values_wave<G, 2, true>(a, d, rows, rows2, lane, slice, dst_tok, s_par, s_par2);
+                else pack_values_wave<G, 1, true>(a, d, rows, rows2, lane, slice, dst_tok, s_par, s_par2);
             }
             return;
         }
     }
     if (!is_v) {
-        if (d.bk == 2) pack_keys_wave<G, 2, false>(a, d, rows, none, lane, bh, dst_tok);
-        else pack_keys_wave<G, 1, false>(a, d, rows, none, lane, bh, dst_tok);
+        if (d.bk == 2) pack_keys_wave<G, 2, false>(a, d, rows, none, lane, slice, dst_tok);
+        else pack_keys_wave<G, 1, false>(a, d, rows, none, lane, slice, dst_tok);
     } else {
-        if (d.bv == 2) pack_values_wave<G, 2, false>(a, d, rows, none, lane, bh, dst_tok, s_par, s_par2);
-        else pack_values_wave<G, 1, false>(a, d, rows, none, lane, bh, dst_tok, s_par, s_par2);
+        if (d.bv == 2) pack_values_wave<G, 2, false>(a, d, rows, none, lane, slice, dst_tok, s_par, s_par2);
+        else pack_values_wave<G, 1, false>(a, d, rows, none, lane, slice, dst_tok, s_par, s_par2);
     }
 }
 
@@ -605,9 +609,10 @@ __global__ __launch_bounds__(256) void xq_unpack_kernel(XqUnpackArgs a) {
     const int B = a.B, per = 32 / B, D = a.D;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         int dd = (int)(idx % D);
-        int t = (int)((idx / D) % a.Tq);
         int bh = (int)(idx / ((int64_t)D * a.Tq));
-        const uint32_t *cp = (const uint32_t *)(a.codes + (int64_t)bh * a.stride);
+        int t;  // token inside the slice that holds it
+        const int64_t slice = xq_locate(a.pg, bh / a.n_kv_heads, bh % a.n_kv_heads, a.n_kv_heads, (int)((idx / D) % a.Tq), &t);
+        const uint32_t *cp = (const uint32_t *)(a.codes + slice * a.stride);
         uint32_t word;
         int bit;
         if (!a.is_v) {
@@ -627,6 +632,12 @@ __global__ __launch_bounds__(256) void xq_unpack_kernel(XqUnpackArgs a) {
 
 __global__ void xq_zero_counts_kernel(unsigned long long *c) { c[threadIdx.x] = 0ull; }
 
+// Page-table entries travel in the kernel arguments, so that a table update is an ordinary
+// launch in the caller's stream (ordered with the kernels that read the table).
+__global__ void xq_page_update_kernel(XqPageUpdateArgs a) {
+    for (int i = threadIdx.x; i < a.n; i += blockDim.x) a.table[a.index[i]] = a.page[i];
+}
+
 // Histogram of |code_a - code_b| over the packed words of two layers (same layout on both
 // sides, so corresponding fields are corresponding elements).  grid.y = (sequence, kv head).
 __global__ __launch_bounds__(256) void xq_delta_histogram_kernel(XqDeltaArgs a) {
@@ -636,11 +647,14 @@ __global__ __launch_bounds__(256) void xq_delta_histogram_kernel(XqDeltaArgs a) 
     const int bh = blockIdx.y;
     const int Tq = a.ragged ? a.seq_Tq[bh / a.n_kv_heads] : a.Tq;
     const int64_t n_words = (int64_t)Tq * a.words_per_token;
-    const uint32_t *wa = (const uint32_t *)(a.codes_a + (int64_t)bh * a.stride);
-    const uint32_t *wb = (const uint32_t *)(a.codes_b + (int64_t)bh * a.stride);
+    const int block_words = 32 * a.words_per_token;  // words of one 32-token block, keys or values
     unsigned int cnt[4] = {0, 0, 0, 0};
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * 256) {
-        const uint32_t x = wa[i], y = wb[i];
+        int tin;
+        const int64_t slice = xq_locate(a.pg, bh / a.n_kv_heads, bh % a.n_kv_heads, a.n_kv_heads,
+                                        (int)(i / block_words) * 32, &tin);
+        const int64_t w = slice * (a.stride / 4) + (int64_t)(tin / 32) * block_words + i % block_words;
+        const uint32_t x = ((const uint32_t *)a.codes_a)[w], y = ((const uint32_t *)a.codes_b)[w];
         if (a.B == 1) {
             const int d1 = __builtin_popcount(x ^ y);
             cnt[1] += d1;
@@ -666,6 +680,12 @@ hipError_t xq_launch_delta_histogram(const XqDeltaArgs &a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     xq_delta_histogram_kernel<<<dim3(64, a.n_bh), dim3(256), 0, s>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t xq_launch_page_update(const XqPageUpdateArgs &a, hipStream_t s) {
+    if (a.n <= 0) return hipSuccess;
+    xq_page_update_kernel<<<dim3(1), dim3(256), 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -1,0 +1,135 @@
+"""Paged caches: the packed tokens of a sequence live in pool pages instead of one region per
+sequence.  What a sequence holds, read page by page, must be the very bytes of the contiguous
+layout (checked against the oracle), and decode must return the same bits as a contiguous cache."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_11236_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tl():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import xq_testlib
+    return xq_testlib
+
+
+def _pages_needed(w, T, P):
+    over = T - w.residual
+    tq = 0 if over <= 0 else w.group * ((over + w.group - 1) // w.group)
+    return (tq + P - 1) // P
+
+
+@pytest.mark.parametrize("D,g,P,rep,T0,n_app", [(128, 32, 128, 1, 1000, 70), (128, 64, 256, 4, 1500, 140),
+                                                (64, 32, 128, 1, 300, 40), (128, 32, 512, 2, 90, 200)])
+def test_paged_equals_contiguous(tl, D, g, P, rep, T0, n_app):
+    w = synth.scaled(synth.workloads()[1 if D == 128 else 0], n_layers=4, batch=3, n_q_heads=2 * rep, n_kv_heads=2,
+                     head_dim=D, group=g, residual=2 * g, kq=2, vq=4, km=0, vm=2, eta1=1 / 6, eta2=0.045, seed=P + D)
+    T = T0 + n_app
+    K, V = synth.kv_all(w, T)
+    Kd, Vd = K.cuda(), V.cuda()
+    need = w.batch * _pages_needed(w, T, P)
+    plain = tl.make_cache(w, max_tokens=T)
+    paged = tl.make_cache(w, max_tokens=T, page_tokens=P, n_pages=need + 3)
+    plain.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    # scramble the page order: occupy and release pages first, then prefill the sequences last to first
+    paged.quantize_pack_seq(Kd[:, 0:1, :, :T0], Vd[:, 0:1, :, :T0], seq0=1)
+    paged.quantize_pack_seq(Kd[:, 0:1, :, :min(T0, 3 * g)], Vd[:, 0:1, :, :min(T0, 3 * g)], seq0=0)
+    paged.reset_seq(1)
+    paged.reset_seq(0)
+    assert paged.free_pages() == need + 3
+    for i in reversed(range(w.batch)):
+        paged.quantize_pack_seq(Kd[:, i:i + 1, :, :T0], Vd[:, i:i + 1, :, :T0], seq0=i)
+    for t in range(T0, T):
+        kn, vn = Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous()
+        plain.append_token(kn, vn)
+        paged.append_token(kn, vn)
+    used = [paged.pages(i) for i in range(w.batch)]
+    assert [len(u) for u in used] == [_pages_needed(w, T, P)] * w.batch
+    flat = [p for u in used for p in u]
+    assert len(set(flat)) == len(flat) and paged.free_pages() == need + 3 - len(flat)
+    if len(flat) > 1:
+        assert flat != sorted(flat)          # the order really is scrambled
+    q = synth.queries(w).cuda()
+    sigma = 1.0 / np.sqrt(D)
+    for flags in (0, 1):
+        for tps in (0, 1):
+            plain.set_tiles_per_split(tps)
+            paged.set_tiles_per_split(tps)
+            assert torch.equal(plain.decode_attention(q, sigma, flags=flags), paged.decode_attention(q, sigma, flags=flags))
+    out = paged.decode_attention(q, sigma, flags=1)
+    for bi in range(w.batch):
+        for h in range(w.n_kv_heads):
+            st = tl.oracle_slice(w, K, V, bi, h)
+            tl.check_stored(paged, w, st, bi, h)
+            tl.check_unpack(paged, w, st, bi, h)
+            tl.check_attention(out, w, tl.oracle_attention(w, st, q, bi, h, sigma), bi, h)
+    # the code-difference histogram walks the pages too (value layers 0 and 1 both keep their codes)
+    assert torch.equal(plain.code_delta_histogram(0, True), paged.code_delta_histogram(0, True))
+    plain.close()
+    paged.close()
+
+
+def test_pool_exhaustion_and_reuse(tl):
+    from paper_2510_11236_amd import XqError
+    w = synth.scaled(synth.workloads()[1], n_layers=2, batch=2, n_q_heads=2, n_kv_heads=2, residual=64, km=0, vm=0,
+                     eta1=1 / 6, eta2=0.045, seed=77)
+    P, T0 = 128, 64 + 3 * 128      # three full pages per sequence after prefill, ring full
+    K, V = synth.kv_all(w, T0 + 200)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=T0 + 200, page_tokens=P, n_pages=7)
+    cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    assert cache.free_pages() == 1
+    # the next append flushes both rings into a fourth page each: one page short
+    kn, vn = Kd[:, :, :, T0].contiguous(), Vd[:, :, :, T0].contiguous()
+    with pytest.raises(XqError) as e:
+        cache.append_token(kn, vn)
+    assert e.value.code == -3
+    assert cache.length(0) == (T0, T0 - 64) and cache.free_pages() == 1      # nothing happened
+    q = synth.queries(w).cuda()
+    before = cache.decode_attention(q, 0.1)
+    # a prefill that does not fit is refused as a whole, too
+    spare = tl.make_cache(w, max_tokens=T0 + 200, page_tokens=P, n_pages=5)
+    with pytest.raises(XqError) as e:
+        spare.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    assert e.value.code == -3 and spare.free_pages() == 5 and spare.length(0) == (0, 0)
+    spare.close()
+    # free sequence 1: sequence 0 can grow again, and a new request can take slot 1
+    cache.reset_seq(1)
+    assert cache.free_pages() == 4
+    cache.quantize_pack_seq(Kd[:, 0:1, :, :100], Vd[:, 0:1, :, :100], seq0=1)  # a short new request in slot 1
+    assert cache.free_pages() == 3
+    for t in range(T0, T0 + 70):
+        cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
+    assert len(cache.pages(0)) == 4 and len(cache.pages(1)) == 1 and cache.free_pages() == 2
+    assert cache.length(0, 0) == (T0 + 70, 480) and cache.length(0, 1) == (170, 128)
+    # oracle check of both sequences (slot 1 holds sequence 0's first 100 tokens + 70 appended ones of sequence 1)
+    st0 = tl.oracle_slice(w, K[:, :, :, :T0 + 70], V[:, :, :, :T0 + 70], 0, 1)
+    tl.check_stored(cache, w, st0, 0, 1)
+    K1 = torch.cat([K[:, 0:1, :, :100], K[:, 1:2, :, T0:T0 + 70]], 3)
+    V1 = torch.cat([V[:, 0:1, :, :100], V[:, 1:2, :, T0:T0 + 70]], 3)
+    st1 = tl.oracle_slice(w, K1, V1, 0, 0)
+    out = cache.decode_attention(q, 0.1)
+    ref = tl.oracle_attention(w, st1, q[:, 1:2], 0, 0, 0.1)
+    for l, r in ref.items():
+        assert float(np.max(np.abs(out[l, 1, 0:1].cpu().numpy() - r))) <= tl.ATOL
+    tl.check_attention(out, w, tl.oracle_attention(w, st0, q, 0, 1, 0.1), 0, 1)
+    assert before.shape == out.shape
+    cache.close()
+
+
+def test_paged_config_checks():
+    from paper_2510_11236_amd import XqError, cache_bytes
+    from paper_2510_11236_amd.binding import config_from_workload
+    w = synth.workloads()[1]
+    for page_tokens, n_pages, code in [(64, 4, -1), (192, 4, -1), (128, 0, -1), (0, 4, -1)]:
+        with pytest.raises(XqError) as e:
+            cache_bytes(config_from_workload(w, 4096, page_tokens, n_pages))
+        assert e.value.code == code
+    a0, _ = cache_bytes(config_from_workload(w, 4096))
+    a1, _ = cache_bytes(config_from_workload(w, 4096, 128, 31))   # 31 pages = the 3968 packed tokens of one sequence
+    assert abs(a1 - a0) < 0.01 * a0

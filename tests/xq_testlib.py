@@ -36,14 +36,14 @@ def check_stored(cache: XqCache, w, state, bi, h, layers=None):
         assert (T, Tq) == (st["T"], st["Tq"]), (l, T, Tq, st["T"], st["Tq"])
         for is_v, pre in ((False, "k"), (True, "v")):
             B = st["b" + pre]
-            meta = cache.region(l, pre + "_meta")[bh].cpu().numpy().view(np.uint32)
+            meta = cache.slice_bytes(l, pre + "_meta", bh).cpu().numpy().view(np.uint32)
             n_meta = (Tq // g) * D if not is_v else Tq * (D // g)
             exp_meta = st[pre + "_scale"].astype(np.uint32).reshape(-1) | (st[pre + "_zero"].astype(np.uint32).reshape(-1) << 16)
             assert np.array_equal(meta[:n_meta], exp_meta), f"layer {l} {pre} metadata differs"
             reg = cache.region(l, pre + "_codes")
             if sch.stores(l, is_v):
                 assert reg is not None
-                words = reg[bh].cpu().numpy().view(np.uint32)[:Tq * D * B // 32]
+                words = cache.slice_bytes(l, pre + "_codes", bh).cpu().numpy().view(np.uint32)[:Tq * D * B // 32]
                 exp = (orc.pack_v_words if is_v else orc.pack_k_words)(st[pre + "_codes"], B)
                 assert np.array_equal(words, exp), f"layer {l} {pre} packed words differ"
             else:
@@ -89,5 +89,5 @@ def check_attention(out, w, ref, bi, h, atol=ATOL):
     return worst
 
 
-def make_cache(w, max_tokens=None, device="cuda:0"):
-    return XqCache(config_from_workload(w, max_tokens), device)
+def make_cache(w, max_tokens=None, device="cuda:0", page_tokens=0, n_pages=0):
+    return XqCache(config_from_workload(w, max_tokens, page_tokens, n_pages), device)
