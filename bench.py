@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "fused"])
+    ap.add_argument("--page-tokens", type=int, default=0,
+                    help="keep the packed tokens in pool pages of this many tokens (0: one region per sequence)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-slices", type=int, default=96)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -132,8 +134,23 @@ def main():
     torch.cuda.set_device(0)
     n_extra = args.warmup + args.steps
     T0 = w.context
-    cfg = config_from_workload(w, max_tokens=T0 + n_extra + 1)
-    cache = XqCache(cfg, dev)
+    if args.page_tokens:
+        P = args.page_tokens
+        tq_max = w.group * ((T0 + n_extra + 1 - w.residual + w.group - 1) // w.group)
+        per_seq = (tq_max + P - 1) // P
+        cfg = config_from_workload(w, max_tokens=T0 + n_extra + 1, page_tokens=P, n_pages=w.batch * per_seq)
+        cache = XqCache(cfg, dev)
+        # hand the pages out in a scrambled order: fill the pool through layer 0 sequence by sequence,
+        # release the sequences in another order (the pool is a stack), then prefill for real
+        dummy = torch.zeros((1, 1, w.n_kv_heads, T0 + n_extra, w.head_dim), dtype=torch.float16, device=dev)
+        for i in range(w.batch):
+            cache.quantize_pack_seq(dummy, dummy, seq0=i)
+        for i in sorted(range(w.batch), key=lambda i: (i * 7 + 3) % w.batch):
+            cache.reset_seq(i)
+        del dummy
+    else:
+        cfg = config_from_workload(w, max_tokens=T0 + n_extra + 1)
+        cache = XqCache(cfg, dev)
     sigma = 1.0 / float(np.sqrt(w.head_dim))
 
     # ---- synthetic KV, packed layer pair by layer pair (also the pack measurement)
@@ -267,7 +284,7 @@ def main():
         "config": {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "context": T0, "group": w.group,
                    "residual": w.residual, "kq": w.kq, "vq": w.vq, "km": w.km, "vm": w.vm,
-                   "schedule": schedule, "step": "append 1 token/sequence + decode attention, all layers in one call"},
+                   "schedule": schedule, "page_tokens": args.page_tokens, "step": "append 1 token/sequence + decode attention, all layers in one call"},
         "roofline": {"bound": "hbm", "kernel": "xq_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms},

@@ -97,3 +97,20 @@ def test_group_and_merge_config_checks(xq):
     # all key layers and 20 value layers stored at 2 bit -> (2 + 1.25) / 2 = 1.625 for G = 2, 3, 4
     for G, vm in ((2, 8), (3, 14), (4, 16)):
         assert xq.equivalent_bits(_cfg(xq, km=32, vm=vm, share_group=G)) == 1.625
+
+
+def test_paged_config_checks(xq):
+    for kw, code in [(dict(page_tokens=64, n_pages=4), -1), (dict(page_tokens=192, n_pages=4), -1),
+                     (dict(page_tokens=128, n_pages=0), -1), (dict(page_tokens=0, n_pages=4), -1)]:
+        with pytest.raises(xq.XqError) as e:
+            xq.cache_bytes(_cfg(xq, **kw))
+        assert e.value.code == code, kw
+    # a pool that holds exactly what the contiguous cache holds costs the same, up to the page table
+    # and the rounding of each sequence to whole pages
+    cfg = _cfg(xq, max_tokens=4096 + 128)              # 4096 packed tokens per sequence
+    a0, _ = xq.cache_bytes(cfg)
+    a1, _ = xq.cache_bytes(_cfg(xq, max_tokens=4096 + 128, page_tokens=128, n_pages=4 * 32))
+    assert abs(a1 - a0) < 0.01 * a0
+    # half the pool: half the packed bytes (the fp16 rings are not paged)
+    a2, _ = xq.cache_bytes(_cfg(xq, max_tokens=4096 + 128, page_tokens=128, n_pages=2 * 32))
+    assert a2 < 0.65 * a0

@@ -120,16 +120,3 @@ def test_pool_exhaustion_and_reuse(tl):
     tl.check_attention(out, w, tl.oracle_attention(w, st0, q, 0, 1, 0.1), 0, 1)
     assert before.shape == out.shape
     cache.close()
-
-
-def test_paged_config_checks():
-    from paper_2510_11236_amd import XqError, cache_bytes
-    from paper_2510_11236_amd.binding import config_from_workload
-    w = synth.workloads()[1]
-    for page_tokens, n_pages, code in [(64, 4, -1), (192, 4, -1), (128, 0, -1), (0, 4, -1)]:
-        with pytest.raises(XqError) as e:
-            cache_bytes(config_from_workload(w, 4096, page_tokens, n_pages))
-        assert e.value.code == code
-    a0, _ = cache_bytes(config_from_workload(w, 4096))
-    a1, _ = cache_bytes(config_from_workload(w, 4096, 128, 31))   # 31 pages = the 3968 packed tokens of one sequence
-    assert abs(a1 - a0) < 0.01 * a0

@@ -1,7 +1,7 @@
 """GPU parity over a seeded sample of the configuration space: head size, group size, ring
 length, bit widths, sharing thresholds, layer groups, query heads per kv head, batch, prompt
-length and number of appended tokens are drawn at random (fixed seeds) within the documented
-limits; stored bytes are compared bit for bit and attention to 2e-3 against the oracle."""
+length, number of appended tokens and contiguous or paged storage are drawn at random (fixed
+seeds) within the documented limits; stored bytes are compared bit for bit and attention to 2e-3 against the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -30,10 +30,13 @@ def _draw(seed):
     batch = int(r.integers(1, 4))
     T0 = int(r.choice([int(r.integers(1, 2 * R + 2)), int(r.integers(1, 1200))]))
     n_app = int(r.choice([0, int(r.integers(1, g + 3)), int(r.integers(1, 3 * g))]))
-    return dict(head_dim=D, group=g, residual=R, n_layers=L, share_group=G, share_dominant=k, kq=kq, vq=vq,
+    page = int(r.choice([0, 0, 128, 256, 1024]))
+    spare = int(r.integers(0, 3))
+    kw = dict(head_dim=D, group=g, residual=R, n_layers=L, share_group=G, share_dominant=k, kq=kq, vq=vq,
                 km=km, vm=vm, merge_mode=merge, gamma0=float(r.choice([0.7, 0.3, 0.5])) if merge == 1 else (0.5 if merge else 1.0),
                 n_q_heads=rep * h_kv, n_kv_heads=h_kv, batch=batch, eta1=float(r.choice([0.0, 1 / 6, 0.2])),
-                eta2=float(r.choice([0.0, 0.045, 0.09]))), T0, n_app
+                eta2=float(r.choice([0.0, 0.045, 0.09])))
+    return kw, T0, n_app, page, spare
 
 
 def _valid(tl, kw):
@@ -54,17 +57,25 @@ def test_random_config(seed):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import xq_testlib as tl
-    kw, T0, n_app = _draw(seed)
+    kw, T0, n_app, page, spare = _draw(seed)
     w = _valid(tl, kw)
     if w is None:
         pytest.skip(f"draw {seed} is not a valid configuration: {kw}")
     w = synth.scaled(w, seed=500 + seed)
-    print(f"seed {seed}: T0={T0} appends={n_app} {kw}", flush=True)
+    print(f"seed {seed}: T0={T0} appends={n_app} page={page} {kw}", flush=True)
     T = T0 + n_app
     K, V = synth.kv_all(w, T)
     Kd, Vd = K.cuda(), V.cuda()
-    cache = tl.make_cache(w, max_tokens=T + 1)
-    cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    if page:
+        # a pool just large enough (plus 0..2 pages); prefill the sequences last to first so that
+        # page numbers do not follow the sequence order
+        tq = 0 if T <= w.residual else w.group * ((T - w.residual + w.group - 1) // w.group)
+        cache = tl.make_cache(w, max_tokens=T + 1, page_tokens=page, n_pages=max(1, w.batch * ((tq + page - 1) // page)) + spare)
+        for i in reversed(range(w.batch)):
+            cache.quantize_pack_seq(Kd[:, i:i + 1, :, :T0], Vd[:, i:i + 1, :, :T0], seq0=i)
+    else:
+        cache = tl.make_cache(w, max_tokens=T + 1)
+        cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
     for t in range(T0, T):
         cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
     q = synth.queries(w).cuda()
