@@ -300,9 +300,19 @@ def main():
         "equivalent_bits": {"paper_definition": equivalent_bits(cfg), "with_metadata_and_ring": equivalent_bits(cfg, True, T0)},
     }
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file):
+    if os.path.exists(traffic_file) and not args.page_tokens:
         try:
-            res["roofline"]["traffic"] = json.load(open(traffic_file)).get(f"{w.name}:{schedule}")
+            prof = json.load(open(traffic_file))
+            res["roofline"]["traffic"] = prof.get(f"{w.name}:{schedule}")
+            insts = prof.get(f"{w.name}:{schedule}:valu_wave_instructions")
+            if insts:
+                # second roof: vector-ALU issue.  Peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
+                # (one instruction per lane per cycle; packed-fp32 forms are not used); achieved = the launch's
+                # counted VALU instructions (SQ_INSTS_VALU, 64 lanes each) over the measured duration.
+                peak = 256 * 4 * 16 * 2.4e9
+                ach = insts * 64 / (decode_ms * 1e-3)
+                res["alu_issue"] = {"achieved": ach, "peak": peak, "unit": "lane-instructions/s", "frac": ach / peak,
+                                    "valu_wave_instructions_per_launch": insts}
         except Exception:
             pass
     if not args.no_cpu_baseline:
