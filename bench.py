@@ -204,8 +204,8 @@ def main():
     out = torch.empty(qs[0].shape, dtype=torch.float32, device=dev)
 
     def time_decode(flags, n=5):
-        for i in range(3):
-            cache.decode_attention(qs[i], sigma, out=out, flags=flags)
+        for i in range(12):     # the clock settles over the first launches after a change of load
+            cache.decode_attention(qs[i % 4], sigma, out=out, flags=flags)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -220,9 +220,9 @@ def main():
     can_fuse = any(l % 2 == 1 and (l >= w.km or l >= w.vm) for l in range(w.n_layers))
     probe = {}
     if args.schedule == "auto":
-        probe["sequential"] = time_decode(0, 10)
+        probe["sequential"] = time_decode(0, 20)
         if can_fuse:
-            probe["fused"] = time_decode(1, 10)
+            probe["fused"] = time_decode(1, 20)
         schedule = min(probe, key=probe.get)
     else:
         schedule = args.schedule if (args.schedule != "fused" or can_fuse) else "sequential"

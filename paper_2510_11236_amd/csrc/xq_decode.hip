@@ -148,7 +148,26 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     const int nbh = a.batch * a.n_kv_heads;
     const int n_main = a.n_splits * nbh * (int)a.n_launch_z;
     int split, bh, lz;
-    if ((int)blockIdx.x < n_main) {
+    if (REUSE && a.pair_order && (int)blockIdx.x < n_main) {
+        // The two layers of a sharing pair read the same code words: their workgroups for one
+        // (split, sequence, kv head) get ids 8 apart -- the same XCD, dispatched at almost the same
+        // time -- so that the second reader finds the words in that XCD's L2.  Ids come in
+        // chunks of 16: eight items of the pair's first layer, then the same eight of its second.
+        const int n_items = n_main / 2, full = (n_items / 8) * 8, id = blockIdx.x;
+        int item, member;
+        if (id < 2 * full) {
+            member = (id % 16) / 8;
+            item = (id / 16) * 8 + id % 8;
+        } else {
+            const int rem = n_items - full, id2 = id - 2 * full;
+            member = id2 / rem;
+            item = full + id2 % rem;
+        }
+        split = item % a.n_splits;
+        const int rest = item / a.n_splits;
+        bh = rest % nbh;
+        lz = 2 * (rest / nbh) + member;
+    } else if ((int)blockIdx.x < n_main) {
         split = blockIdx.x % a.n_splits;
         const int rest = blockIdx.x / a.n_splits;
         bh = rest % nbh;

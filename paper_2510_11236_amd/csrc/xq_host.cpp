@@ -161,13 +161,17 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
     return (size_t)n_layers * c.batch * c.n_q_heads * (size_t)(n_splits + 1) * (c.head_dim + 2);
 }
 
-// Split plan: whole tiles of 128 tokens per split, equal-sized splits.  A workgroup pays a
-// fixed cost (prologue, cross-wave combine, partial write: about 3 tiles' worth) and the chip
-// holds about 1024 workgroups at once (256 CUs x 4), so the plan minimises
-//   rounds(n) * (tiles per split + 3),  rounds(n) = ceil(slices * n / 1024)
-// over the number of splits n, with at least one tile per wave and at most XQ_MAX_SPLITS.
-void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int *tiles_per_split) {
-    const xq_config &c = cache->cfg;
+// Split plan: whole tiles of 128 tokens per split, equal-sized splits.  work_items = the
+// (layer or fused pair, sequence, kv head) slices the call's launches cover; each becomes n
+// workgroups of t tiles.  A workgroup pays a fixed cost (prologue, cross-wave combine, partial
+// write: about 3 tiles' worth) and the chip holds about 1024 workgroups at once (256 CUs x 4).
+// Workgroups are dealt out as slots free up, so a launch takes about
+//   (t + 3) * (max(items * n / 1024, 1) + 0.2)
+// tile times: the work spread over the slots (a launch that does not fill them still takes one
+// workgroup's time) plus a fifth of a workgroup of ragged tail (fitted to sweeps of the 4k,
+// 16k, 32k and 256k configurations).  The plan minimises that over n, with
+// at least four tiles per split (one per wave) where the length allows and at most XQ_MAX_SPLITS.
+void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_splits, int *tiles_per_split) {
     int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
     if (tiles == 0) {
         *n_splits = 0;
@@ -178,15 +182,14 @@ void plan_splits(const xq_cache *cache, int Tq, int n_layers, int *n_splits, int
     if (cache->tiles_per_split_override > 0) {
         tps = cache->tiles_per_split_override;
     } else {
-        const int64_t slices = (int64_t)c.batch * c.n_kv_heads * n_layers;
         int most = (tiles + 3) / 4;
         if (most > XQ_MAX_SPLITS) most = XQ_MAX_SPLITS;
-        int64_t best_cost = -1;
+        double best_cost = -1.0;
         tps = tiles;
         for (int n = 1; n <= most; ++n) {
             const int t = (tiles + n - 1) / n;
-            const int64_t rounds = (slices * ((tiles + t - 1) / t) + 1023) / 1024;
-            const int64_t cost = rounds * (t + 3);
+            const double fill = (double)work_items * ((tiles + t - 1) / t) / 1024.0;
+            const double cost = (t + 3) * ((fill > 1.0 ? fill : 1.0) + 0.2);
             if (best_cost < 0 || cost < best_cost) {
                 best_cost = cost;
                 tps = t;
@@ -596,12 +599,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
     const bool ragged = !row_uniform(cache, layer0);
     if (ragged && c.batch > XQ_MAX_RAGGED) return XQ_ERR_UNSUPPORTED;
     const int Tq = xq_quantized_len(T, c.group, c.residual);
-    int n_splits, tps;
-    plan_splits(cache, Tq, n_layers, &n_splits, &tps);
-    if (workspace_floats(c, n_layers, n_splits) * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)hip_stream;
-    const int64_t per_layer_q = (int64_t)c.batch * c.n_q_heads * c.head_dim;
-    const int64_t per_layer_ws = (int64_t)c.batch * c.n_q_heads * (n_splits + 1) * (c.head_dim + 2);
     const int rep = c.n_q_heads / c.n_kv_heads;
     // The kernels serve 1, 2 or 4 query heads of a kv head at a time (1 when D = 64): other
     // ratios take several passes over the kv head's cache, largest part first.
@@ -610,20 +608,25 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         parts[n_parts] = (c.head_dim == 64) ? 1 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1));
     bool fusable = true;  // a pair shares a workgroup only if every part fits the kernel's weight tables
     for (int i = 0; i < n_parts; ++i) fusable = fusable && xq_decode_can_fuse(c.head_dim, c.group, parts[i]);
+    // whether one workgroup serves the pair (a, a+1): only when the second layer reads both the
+    // key and the value codes of the first (with one of the two shared, holding two code sets
+    // in registers costs more than the shared unpacking saves: measured 12 % slower)
+    auto fuse_mode = [&](int a) -> int {
+        if (!(flags & XQ_DECODE_PAIR_FUSED) || !fusable) return 0;
+        if (group_size(c) != 2 || c.share_dominant != 0) return 0;
+        if (a % 2 != 0 || a + 1 >= layer0 + n_layers) return 0;
+        if (cache->layers[a + 1].bk != cache->layers[a].bk || cache->layers[a + 1].bv != cache->layers[a].bv) return 0;
+        return (!cache->layers[a + 1].k_store && !cache->layers[a + 1].v_store) ? 1 : 0;
+    };
     // runs of layers with one (bk, bv) and one fusion mode share a launch
-    int l = layer0;
-    while (l < layer0 + n_layers) {
+    struct Run {
+        int l, e, fused;
+    };
+    Run runs[XQ_MAX_LAYERS];
+    int n_runs = 0;
+    int64_t work_items = 0;  // (layer or pair, sequence, kv head) slices = workgroups per split
+    for (int l = layer0; l < layer0 + n_layers;) {
         const XqLayerDesc &d0 = cache->layers[l];
-        // whether one workgroup serves the pair (a, a+1): only when the second layer reads both the
-        // key and the value codes of the first (with one of the two shared, holding two code sets
-        // in registers costs more than the shared unpacking saves: measured 12 % slower)
-        auto fuse_mode = [&](int a) -> int {
-            if (!(flags & XQ_DECODE_PAIR_FUSED) || !fusable) return 0;
-            if (group_size(c) != 2 || c.share_dominant != 0) return 0;
-            if (a % 2 != 0 || a + 1 >= layer0 + n_layers) return 0;
-            if (cache->layers[a + 1].bk != cache->layers[a].bk || cache->layers[a + 1].bv != cache->layers[a].bv) return 0;
-            return (!cache->layers[a + 1].k_store && !cache->layers[a + 1].v_store) ? 1 : 0;
-        };
         const int fused = fuse_mode(l);
         int e = l;
         while (e < layer0 + n_layers) {
@@ -637,6 +640,18 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
                 e += 1;
             }
         }
+        runs[n_runs++] = Run{l, e, fused};
+        work_items += (int64_t)(fused ? (e - l) / 2 : e - l) * c.batch * c.n_kv_heads;
+        l = e;
+    }
+    int n_splits, tps;
+    plan_splits(cache, Tq, work_items, &n_splits, &tps);
+    if (workspace_floats(c, n_layers, n_splits) * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
+    const int64_t per_layer_q = (int64_t)c.batch * c.n_q_heads * c.head_dim;
+    const int64_t per_layer_ws = (int64_t)c.batch * c.n_q_heads * (n_splits + 1) * (c.head_dim + 2);
+    for (int ri = 0; ri < n_runs; ++ri) {
+        const int l = runs[ri].l, e = runs[ri].e, fused = runs[ri].fused;
+        const XqLayerDesc &d0 = cache->layers[l];
         XqDecodeArgs a;
         memset(&a, 0, sizeof(a));
         a.arena = cache->arena;
@@ -663,6 +678,8 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;
             }
+        // the run is a whole number of (even, odd) pairs, some of which share codes
+        a.pair_order = a.reuse_codes && group_size(c) == 2 && c.share_dominant == 0 && l % 2 == 0 && (e - l) % 2 == 0;
         a.rep = rep;
         for (int i = 0; i < n_parts; ++i) {
             if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, parts[i], e - l, fused, s) != hipSuccess)
@@ -670,7 +687,6 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
             a.q_head0 += parts[i];
         }
         if (xq_launch_merge(a, c.head_dim, e - l, s) != hipSuccess) return XQ_ERR_HIP;
-        l = e;
     }
     return XQ_OK;
 }

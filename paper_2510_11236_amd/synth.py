@@ -57,6 +57,9 @@ def workloads():
         # (configuration table: kq=30, vq=2, km=32, vm=16 -> 1.375 equivalent bits) on the 7B shape
         Workload("paper_main_schedule_7b_32k_b4", 32, 4, 32, 32, 128, 32768, 32, 128, 30, 2, 32, 16,
                  1.0 / 6.0, 0.045, 5),
+        # scaling checks on the 7B shape with all pairs shared: one very long sequence; a large batch
+        Workload("long_7b_256k_b1_shared", 32, 1, 32, 32, 128, 262144, 32, 128, 32, 32, 0, 0, 1.0 / 6.0, 0.045, 6),
+        Workload("wide_7b_32k_b16_shared", 32, 16, 32, 32, 128, 32768, 32, 128, 32, 32, 0, 0, 1.0 / 6.0, 0.045, 7),
     ]
 
 
