@@ -237,7 +237,9 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
         // hit the same memory channels at once.  Softmax accumulation does not care about order.
         const int tile0 = split * a.tiles_per_split;
         const int n_tiles = max(min(tile0 + a.tiles_per_split, (n_blocks + 3) / 4) - tile0, 0);  // 0: a shorter sequence
-        const int rot = n_tiles > 0 ? (int)((bh * 37u + lz * 11u) % (unsigned)n_tiles) : 0;
+        // (the two layers of a pair that run side by side start at the same tile: they read the same codes)
+        const int lrot = (REUSE && a.pair_order) ? lz / 2 : lz;
+        const int rot = n_tiles > 0 ? (int)((bh * 37u + lrot * 11u) % (unsigned)n_tiles) : 0;
         for (int it = wave; it < n_tiles; it += 4) {
             const int tile = tile0 + (it + rot) % n_tiles;
             const int blk = tile * 4 + row;
