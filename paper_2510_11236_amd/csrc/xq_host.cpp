@@ -163,14 +163,17 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 
 // Split plan: whole tiles of 128 tokens per split, equal-sized splits.  work_items = the
 // (layer or fused pair, sequence, kv head) slices the call's launches cover; each becomes n
-// workgroups of t tiles.  A workgroup pays a fixed cost (prologue, cross-wave combine, partial
-// write: about 3 tiles' worth) and the chip holds about 1024 workgroups at once (256 CUs x 4).
-// Workgroups are dealt out as slots free up, so a launch takes about
-//   (t + 3) * (max(items * n / 1024, 1) + 0.2)
+// workgroups of t tiles.  A workgroup pays a fixed cost (launch, prologue, cross-wave combine,
+// partial write and its share of the merge: about 8 tiles' worth) and the chip holds about 1024
+// workgroups at once (256 CUs x 4).  Workgroups are dealt out as slots free up, so a launch takes
+// about
+//   (t + 8) * (rounds + 0.2),   rounds = items * n / 1024, at least 1,
 // tile times: the work spread over the slots (a launch that does not fill them still takes one
-// workgroup's time) plus a fifth of a workgroup of ragged tail (fitted to sweeps of the 4k,
-// 16k, 32k and 256k configurations).  The plan minimises that over n, with
-// at least four tiles per split (one per wave) where the length allows and at most XQ_MAX_SPLITS.
+// workgroup's time; a small number of rounds is rounded up towards a whole number, because equal
+// workgroups finish together) plus a fifth of a workgroup of ragged tail.  The constants are fitted to
+// sweeps of n on the 4k, 16k, 32k and 256k configurations, all layers per call and one layer per
+// call.  The plan minimises that over n, with at least four tiles per split (one per wave) where
+// the length allows and at most XQ_MAX_SPLITS.
 void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_splits, int *tiles_per_split) {
     int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
     if (tiles == 0) {
@@ -189,7 +192,10 @@ void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_split
         for (int n = 1; n <= most; ++n) {
             const int t = (tiles + n - 1) / n;
             const double fill = (double)work_items * ((tiles + t - 1) / t) / 1024.0;
-            const double cost = (t + 3) * ((fill > 1.0 ? fill : 1.0) + 0.2);
+            // few rounds come in whole numbers (equal workgroups finish together); many rounds even out
+            const double whole = ceil(fill), blend = fill < 8.0 ? 1.0 - fill / 8.0 : 0.0;
+            const double rounds = fill <= 1.0 ? 1.0 : fill + (whole - fill) * blend;
+            const double cost = (t + 8) * (rounds + 0.2);
             if (best_cost < 0 || cost < best_cost) {
                 best_cost = cost;
                 tps = t;
