@@ -172,8 +172,7 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 // workgroup's time; a small number of rounds is rounded up towards a whole number, because equal
 // workgroups finish together) plus a fifth of a workgroup of ragged tail.  The constants are fitted to
 // sweeps of n on the 4k, 16k, 32k and 256k configurations, all layers per call and one layer per
-// call.  The plan minimises that over n, with at least four tiles per split (one per wave) where
-// the length allows and at most XQ_MAX_SPLITS.
+// call.  The plan minimises that over n, with at most XQ_MAX_SPLITS splits.
 void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_splits, int *tiles_per_split) {
     int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
     if (tiles == 0) {
@@ -185,7 +184,11 @@ void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_split
     if (cache->tiles_per_split_override > 0) {
         tps = cache->tiles_per_split_override;
     } else {
-        int most = (tiles + 3) / 4;
+        // splits of at least 16 tiles (four per wave); shorter ones, down to one tile per wave,
+        // only while the launch would otherwise stay below 256 workgroups
+        int min_t = 16;
+        while (min_t > 4 && work_items * ((tiles + min_t - 1) / min_t) < 256) min_t /= 2;
+        int most = (tiles + min_t - 1) / min_t;
         if (most > XQ_MAX_SPLITS) most = XQ_MAX_SPLITS;
         double best_cost = -1.0;
         tps = tiles;
