@@ -559,3 +559,39 @@ def test_maximum_counts(lib_):
                      eta2=0.045, seed=67)
     worst = max(worst, _run_prefill_case(tl, w, 400))
     print("maximum counts worst attention error", worst)
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_prior_memory_contents_do_not_matter(lib_, paged):
+    """The arena and the workspace need no initialisation: whatever they held before (zeros, 0xFF
+    bytes = NaN halves and all-ones codes, random bytes), outputs come out bit-identical."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[1], n_layers=4, batch=2, n_q_heads=4, n_kv_heads=2, km=0, vm=2, eta1=1 / 6,
+                     eta2=0.045, seed=321)
+    T0, n_app = 700, 45
+    K, V = synth.kv_all(w, T0 + n_app)
+    Kd, Vd = K.cuda(), V.cuda()
+    q = synth.queries(w).cuda()
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    results = []
+    for fill in ("zero", "ff", "random"):
+        cache = tl.make_cache(w, max_tokens=T0 + n_app, page_tokens=128 if paged else 0, n_pages=14 if paged else 0)
+        for buf in [cache.workspace] + [cache.region(l, n) for l in range(w.n_layers)
+                                        for n in ("k_codes", "v_codes", "k_meta", "v_meta", "k_res", "v_res")]:
+            if buf is None:
+                continue
+            if fill == "zero":
+                buf.zero_()
+            elif fill == "ff":
+                buf.fill_(0xff)
+            else:
+                buf.copy_(torch.randint(0, 256, buf.shape, dtype=torch.uint8, device="cuda", generator=gen))
+        cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+        for t in range(T0, T0 + n_app):
+            cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
+        results.append([cache.decode_attention(q, 0.09, flags=f).clone() for f in (0, 1)])
+        torch.cuda.synchronize()
+        cache.close()
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert torch.equal(a, b)
