@@ -511,19 +511,24 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
     }
 }
 
-// grid.x = 2 * token groups (first half: keys, second half: values -- kept apart because
-// workgroups are dealt round-robin to the 8 XCDs and the two kinds cost differently),
-// grid.y = sequence * kv head, grid.z = layer
+// One wave per item, XQ_PACK_WAVES waves per workgroup along grid.x; items 0 .. n_groups - 1 are
+// the key groups, n_groups .. 2 n_groups - 1 the value groups (kept apart because workgroups are
+// dealt round-robin to the 8 XCDs and the two kinds cost differently); grid.y = sequence * kv head,
+// grid.z = layer.
 // MG: built for caches whose sharing pairs store merged codes (Appendix E); a wave of the
 // pair's first layer then also reads the second layer's rows.
+#define XQ_PACK_WAVES 4   // waves (= token groups) per workgroup
 template <int G, bool MG = false>
-__global__ __launch_bounds__(64) void xq_pack_wave_kernel(XqPackArgs a) {
+__global__ __launch_bounds__(64 * XQ_PACK_WAVES) void xq_pack_wave_kernel(XqPackArgs a) {
     constexpr int D = 128;
-    __shared__ float4 s_par[G * (D / G)];
-    __shared__ float4 s_par2[MG ? G * (D / G) : 1];
-    const int lane = threadIdx.x;
-    const bool is_v = (int)blockIdx.x >= a.n_groups;
-    const int grp = is_v ? blockIdx.x - a.n_groups : blockIdx.x;
+    __shared__ float4 s_par_all[XQ_PACK_WAVES][G * (D / G)];
+    __shared__ float4 s_par2_all[XQ_PACK_WAVES][MG ? G * (D / G) : 1];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    float4 *s_par = s_par_all[wave], *s_par2 = s_par2_all[wave];
+    const int item = blockIdx.x * XQ_PACK_WAVES + wave;
+    if (item >= 2 * a.n_groups) return;
+    const bool is_v = item >= a.n_groups;
+    const int grp = is_v ? item - a.n_groups : item;
     const int bh = a.bh0 + blockIdx.y, lz = blockIdx.z;
     const XqLayerDesc d = a.layers[a.layer0 + lz];
     const int bi = blockIdx.y / a.n_kv_heads, hh = blockIdx.y % a.n_kv_heads;  // source indices are local to the call
@@ -692,7 +697,7 @@ hipError_t xq_launch_page_update(const XqPageUpdateArgs &a, hipStream_t s) {
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s) {
     if (a.n_groups <= 0) return hipSuccess;
     dim3 grid(a.n_groups, a.batch * a.n_kv_heads, n_layers), block(256);
-    dim3 wgrid(2 * a.n_groups, a.batch * a.n_kv_heads, n_layers), wblock(64);
+    dim3 wgrid((2 * a.n_groups + XQ_PACK_WAVES - 1) / XQ_PACK_WAVES, a.batch * a.n_kv_heads, n_layers), wblock(64 * XQ_PACK_WAVES);
     if (D == 128 && g == 32 && !a.merge) xq_pack_wave_kernel<32><<<wgrid, wblock, 0, s>>>(a);
     else if (D == 128 && g == 64 && !a.merge) xq_pack_wave_kernel<64><<<wgrid, wblock, 0, s>>>(a);
     else if (D == 128 && g == 32) xq_pack_wave_kernel<32, true><<<wgrid, wblock, 0, s>>>(a);
