@@ -366,8 +366,11 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     const GroupQ qa = group_quant<B>(pair_min(pa), pair_max(pa), c1, c2, &ma);
     const GroupQ qb = group_quant<B>(pair_min(pb), pair_max(pb), c1, c2, &mb);
     uint32_t *mp = (uint32_t *)(a.arena + d.k_meta + slice * a.st.k_meta) + (int64_t)(dst_tok / G) * D + 2 * lane;
-    __builtin_nontemporal_store(ma, mp);  // streamed out once: keep it out of the way of the reads
-    __builtin_nontemporal_store(mb, mp + 1);
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 mab;
+    mab.x = ma;
+    mab.y = mb;
+    __builtin_nontemporal_store(mab, (u32x2 *)mp);  // streamed out once: keep it out of the way of the reads
     if (!d.k_store) return;
     GroupQ q2a = qa, q2b = qb;  // the next layer's own groups (its metadata is written by its own wave)
     if constexpr (MG) {
@@ -506,8 +509,11 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
             words[m] = w;
         }
         uint32_t *wp = cp + (int64_t)(dst_tok / 32 + blk) * 64 * WS + lane * WS;
+        typedef uint32_t u32xw __attribute__((ext_vector_type(WS)));
+        u32xw wv;
 #pragma unroll
-        for (int m = 0; m < WS; ++m) __builtin_nontemporal_store(words[m], wp + m);
+        for (int m = 0; m < WS; ++m) wv[m] = words[m];
+        __builtin_nontemporal_store(wv, (u32xw *)wp);
     }
 }
 
