@@ -263,6 +263,69 @@ def test_sharing_identical_layers_equals_unshared(oracle):
         assert np.array_equal(a, b)
 
 
+def test_layer_groups_read_the_dominant_layers_codes(oracle):
+    """Sec. 4.3 "Group Size": in a group of G layers every layer is dequantized with the codes of
+    the group's k-th layer and its own scale and zero-point.  Layers that differ only by a positive
+    power-of-two factor have identical own codes, so each must decode exactly as it would unshared;
+    one layer with different data in the dominant position must change its readers' results."""
+    rng = np.random.default_rng(16)
+    T, D, L = 128, 64, 7
+    K0 = rng.standard_normal((T, D)).astype(np.float16)
+    V0 = rng.standard_normal((T, D)).astype(np.float16)
+    scale = [1.0, 2.0, 8.0, 4.0, 1.0, 16.0, 2.0]
+    K = np.stack([(K0.astype(np.float32) * a).astype(np.float16) for a in scale])
+    V = np.stack([(V0.astype(np.float32) * a).astype(np.float16) for a in scale])
+    q = rng.standard_normal((1, D)).astype(np.float16)
+    plain_s = oracle.Schedule(L, L, L, L, L, 0.0, 0.045, 32, 32)
+    plain = oracle.cache_slice(plain_s, K, V)
+    for G, k in ((3, 1), (4, 3), (3, 0)):
+        s = oracle.Schedule(L, L, L, 0, 0, 0.0, 0.045, 32, 32, G, k)
+        st = oracle.cache_slice(s, K, V)
+        for l in range(L):
+            assert (st[l]["k_codes"] is not None) == (s.code_layer(l, False) == l)
+            assert np.array_equal(oracle.decode_slice(s, st, l, q, 0.125), oracle.decode_slice(plain_s, plain, l, q, 0.125)), (G, k, l)
+        # now the dominant layer of the first group holds other data: its readers follow it
+        K2, V2 = K.copy(), V.copy()
+        K2[k] = rng.standard_normal((T, D)).astype(np.float16)
+        st2 = oracle.cache_slice(s, K2, V)
+        reader = 0 if k != 0 else 1
+        Kh, _ = oracle.dequant_slice(s, st2, reader)
+        own = oracle.dequant_k(st2[k]["k_codes"], st2[reader]["k_scale"], st2[reader]["k_zero"], 32)
+        assert np.array_equal(Kh[:own.shape[0]], own)
+        assert not np.array_equal(oracle.decode_slice(s, st2, reader, q, 0.125), oracle.decode_slice(plain_s, plain, reader, q, 0.125))
+
+
+def test_merged_pair_stores_the_merge_of_both_layers_own_codes(oracle):
+    """Appendix E: a merged pair stores e_m = round(gamma0 e_0 + (1 - gamma0) e_1) of the two layers'
+    OWN codes.  gamma0 = 1 keeps the first layer's codes, gamma0 = 0 the second layer's, and in
+    between the stored tensor is the element-wise merge of what each layer stores unshared."""
+    rng = np.random.default_rng(26)
+    T, D = 128, 64
+    K = rng.standard_normal((2, T, D)).astype(np.float16)
+    V = rng.standard_normal((2, T, D)).astype(np.float16)
+    plain = oracle.cache_slice(oracle.Schedule(2, 2, 2, 2, 2, 1 / 6, 0.045, 32, 32), K, V)
+    assert not np.array_equal(plain[0]["k_codes"], plain[1]["k_codes"])
+    for mode, g0 in ((1, 1.0), (1, 0.0), (1, 0.7), (1, 0.3), (2, 0.5), (3, 0.5)):
+        s = oracle.Schedule(2, 2, 2, 0, 0, 1 / 6, 0.045, 32, 32, 2, 0, mode, g0)
+        st = oracle.cache_slice(s, K, V)
+        assert st[1]["k_codes"] is None and st[1]["v_codes"] is None
+        for pre in ("k", "v"):
+            e0, e1 = plain[0][pre + "_codes"].astype(int), plain[1][pre + "_codes"].astype(int)
+            if mode == 1:
+                want = np.floor(g0 * e0 + (1 - g0) * e1 + 0.5)
+            elif mode == 2:
+                want = (e0 + e1) // 2
+            else:
+                want = (e0 + e1 + 1) // 2
+            assert np.array_equal(st[0][pre + "_codes"], want.astype(np.uint8)), (mode, g0, pre)
+            # both layers keep their own scale and zero-point
+            for l in (0, 1):
+                assert np.array_equal(st[l][pre + "_scale"], plain[l][pre + "_scale"])
+                assert np.array_equal(st[l][pre + "_zero"], plain[l][pre + "_zero"])
+    s = oracle.Schedule(2, 2, 2, 0, 0, 1 / 6, 0.045, 32, 32, 2, 0, 1, 0.0)
+    assert np.array_equal(oracle.cache_slice(s, K, V)[0]["k_codes"], plain[1]["k_codes"])
+
+
 def test_sharing_affine_layers_lossless(oracle):
     """X_1 = a*X_0 + b with a a power of two > 0: layer 1's own codes would equal layer
     0's, so sharing loses nothing; a < 0 mirrors the codes (n - c)."""
