@@ -149,24 +149,25 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     const int n_main = a.n_splits * nbh * (int)a.n_launch_z;
     int split, bh, lz;
     if (REUSE && a.pair_order && (int)blockIdx.x < n_main) {
-        // The two layers of a sharing pair read the same code words: their workgroups for one
-        // (split, sequence, kv head) get ids 8 apart -- the same XCD, dispatched at almost the same
-        // time -- so that the second reader finds the words in that XCD's L2.  Ids come in
-        // chunks of 16: eight items of the pair's first layer, then the same eight of its second.
-        const int n_items = n_main / 2, full = (n_items / 8) * 8, id = blockIdx.x;
+        // The G layers of a sharing group (G = a.pair_order; a pair when 2) read the same code
+        // words: their workgroups for one (split, sequence, kv head) get ids 8 apart -- the same
+        // XCD, dispatched at almost the same time -- so that the later readers find the words in
+        // that XCD's L2.  Ids come in chunks of 8 G: eight items of the group's first layer, then
+        // the same eight of its second, ...
+        const int G_ = a.pair_order, n_items = n_main / G_, full = (n_items / 8) * 8, id = blockIdx.x;
         int item, member;
-        if (id < 2 * full) {
-            member = (id % 16) / 8;
-            item = (id / 16) * 8 + id % 8;
+        if (id < G_ * full) {
+            member = (id % (8 * G_)) / 8;
+            item = (id / (8 * G_)) * 8 + id % 8;
         } else {
-            const int rem = n_items - full, id2 = id - 2 * full;
+            const int rem = n_items - full, id2 = id - G_ * full;
             member = id2 / rem;
             item = full + id2 % rem;
         }
         split = item % a.n_splits;
         const int rest = item / a.n_splits;
         bh = rest % nbh;
-        lz = 2 * (rest / nbh) + member;
+        lz = G_ * (rest / nbh) + member;
     } else if ((int)blockIdx.x < n_main) {
         split = blockIdx.x % a.n_splits;
         const int rest = blockIdx.x / a.n_splits;
@@ -237,8 +238,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
         // hit the same memory channels at once.  Softmax accumulation does not care about order.
         const int tile0 = split * a.tiles_per_split;
         const int n_tiles = max(min(tile0 + a.tiles_per_split, (n_blocks + 3) / 4) - tile0, 0);  // 0: a shorter sequence
-        // (the two layers of a pair that run side by side start at the same tile: they read the same codes)
-        const int lrot = (REUSE && a.pair_order) ? lz / 2 : lz;
+        // (the layers of a group that run side by side start at the same tile: they read the same codes)
+        const int lrot = (REUSE && a.pair_order) ? lz / a.pair_order : lz;
         const int rot = n_tiles > 0 ? (int)((bh * 37u + lrot * 11u) % (unsigned)n_tiles) : 0;
         for (int it = wave; it < n_tiles; it += 4) {
             const int tile = tile0 + (it + rot) % n_tiles;

@@ -687,8 +687,8 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;
             }
-        // the run is a whole number of (even, odd) pairs, some of which share codes
-        a.pair_order = a.reuse_codes && group_size(c) == 2 && c.share_dominant == 0 && l % 2 == 0 && (e - l) % 2 == 0;
+        // the run is a whole number of sharing groups (pairs by default), some of which share codes
+        a.pair_order = (a.reuse_codes && l % group_size(c) == 0 && (e - l) % group_size(c) == 0) ? group_size(c) : 0;
         a.rep = rep;
         for (int i = 0; i < n_parts; ++i) {
             if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, parts[i], e - l, fused, s) != hipSuccess)
