@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "fused"])
     ap.add_argument("--page-tokens", type=int, default=0,
                     help="keep the packed tokens in pool pages of this many tokens (0: one region per sequence)")
+    ap.add_argument("--vector-alu", action="store_true",
+                    help="decode with the vector-ALU kernels instead of the matrix-instruction ones")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-slices", type=int, default=96)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -217,16 +219,17 @@ def main():
 
     # --schedule auto times both schedules (untimed probes) and takes the faster; an explicit
     # schedule runs no probes, so that a profile of the run holds only warmup + timed launches
+    alu = 2 if args.vector_alu else 0
     can_fuse = any(l % 2 == 1 and (l >= w.km or l >= w.vm) for l in range(w.n_layers))
     probe = {}
     if args.schedule == "auto":
-        probe["sequential"] = time_decode(0, 20)
+        probe["sequential"] = time_decode(alu, 20)
         if can_fuse:
-            probe["fused"] = time_decode(1, 20)
+            probe["fused"] = time_decode(1 | alu, 20)
         schedule = min(probe, key=probe.get)
     else:
         schedule = args.schedule if (args.schedule != "fused" or can_fuse) else "sequential"
-    flags = 1 if schedule == "fused" else 0
+    flags = (1 if schedule == "fused" else 0) | alu
     by_schedule = {}
     for name, ms in probe.items():
         ab = algorithmic_bytes(w, T0, fused=(name == "fused"))
@@ -275,7 +278,7 @@ def main():
     T_mid = T0 + args.warmup + (args.steps + 1) // 2
     kv_tok_s = w.batch * T_mid / (ms_per_step * 1e-3)
 
-    alg = algorithmic_bytes(w, T_mid, fused=bool(flags))
+    alg = algorithmic_bytes(w, T_mid, fused=bool(flags & 1))
     achieved = alg / (decode_ms * 1e-3) / 1e9
     res = {
         "metric": "decode_attention_kv_tokens_per_s", "value": kv_tok_s, "unit": "KV tokens/s", "n_gpus": 1,

@@ -183,6 +183,11 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * that share only one of the two, or not at all, run one layer per workgroup as without it).  All layers in the range must hold
  * the same, non-zero number of tokens per sequence (sequences may differ from one another). */
 #define XQ_DECODE_PAIR_FUSED 1
+/* With head_dim 128 the multiply-adds run on the 4x4x4 fp16 matrix instruction (rows = query
+ * heads of the kv head and layers of the pair, times the two fp16 halves of a key weight);
+ * XQ_DECODE_VECTOR_ALU selects the kernels that do them on the vector ALU instead (always
+ * used for head_dim 64).  Both meet the same error bound. */
+#define XQ_DECODE_VECTOR_ALU 2
 int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
                         void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                         int32_t flags, void *hip_stream);

@@ -26,6 +26,9 @@
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float hbits(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
 
@@ -46,6 +49,39 @@ __device__ __forceinline__ float fma_mix_lo(float w, uint32_t c, float acc) {
 __device__ __forceinline__ float fma_mix_hi(float w, uint32_t c, float acc) {
     asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(acc) : "v"(w), "v"(c));
     return acc;
+}
+
+// The 4x4x4 matrix instruction as a four-row dot-product unit: 16 blocks of 4 lanes; in a block,
+// lane j supplies column j of B (4 halves) and receives column j of the 4x4 result (one row per
+// register); the A rows (4 halves each) come from lane i of block ABID of the lane's group of
+// 2^CB blocks, so one register pair holds 2^CB different A matrices.
+template <int CB>
+__device__ __forceinline__ float4_t mfma_rows(half4_t a, half4_t b, float4_t c, int abid) {
+    switch (abid) {
+        case 0: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 0, 0);
+        case 1: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 1, 0);
+        case 2: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 2, 0);
+        case 3: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 3, 0);
+    }
+    if constexpr (CB == 3) {
+        switch (abid) {
+            case 4: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 4, 0);
+            case 5: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 5, 0);
+            case 6: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 6, 0);
+            case 7: return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, CB, 7, 0);
+        }
+    }
+    return c;
+}
+__device__ __forceinline__ half4_t codes4(uint32_t lo, uint32_t hi) {
+    uint2_t u = {lo, hi};
+    return __builtin_bit_cast(half4_t, u);
+}
+template <int W>
+__device__ __forceinline__ uint32_t group_umax(uint32_t v) {  // max over aligned groups of W lanes
+#pragma unroll
+    for (int o = W / 2; o >= 1; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
+    return v;
 }
 
 template <int W>
@@ -102,7 +138,16 @@ __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp
 
 // NLAY = 2: the two layers of a sharing pair (one key and one value code tensor, read by the
 // first layer's descriptor) are served by one workgroup.
-template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false>
+//
+// MM = true (D = 128): the multiply-adds go through the 4x4x4 fp16 matrix instruction, used as a
+// four-row dot-product unit whose rows are (virtual head, half of the weight) pairs.  The lane
+// still owns its tokens (keys) or channels (values): the codes it isolated are its column of B,
+// four at a time, and the weights are the rows of A, which every block of the lane's token group
+// (keys) or channel group (values) takes from one block of a register pair by broadcast.  Key
+// weights are split into an fp16 high and low part (two rows) after a per-group power-of-two
+// scaling, which keeps ~22 bits of them for any input; value weights are the same fp16 numbers
+// as in the plain path.
+template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false, bool MM = false>
 __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane
@@ -122,20 +167,32 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     constexpr uint32_t MASKK = ((1u << BK) - 1u) * 0x00010001u;
     constexpr uint32_t MASKV = ((1u << BV) - 1u) * 0x00010001u;
     static_assert(CPP >= 2 && CPP <= 8, "prep width");
+    constexpr int CPB = BYTEK / 4;        // chunks of 4 code positions per byte (keys)
+    // matrix path: blocks of 4 lanes per token group = per value channel group (D = tile = 128)
+    constexpr int NB = 16 / NGT;
+    constexpr int CBSZ = NB == 8 ? 3 : 2;
+    constexpr int NKS = (2 * NV + 3) / 4;  // sets of 4 key rows (head, weight half)
+    constexpr int NVS = (NV + 3) / 4;      // sets of 4 value rows (head)
+    constexpr int AREG = 32 / NB;          // register pairs that hold the 32 A matrices of a row set
+    constexpr int NPL = CPP / 4;           // key A matrices one lane prepares
+    constexpr int QPW = TPW / 4;           // token quads per value word
+    static_assert(!MM || (D == 128 && (NB == 8 || NB == 4)), "matrix path shape");
 
     // per wave: key weights q * s^ (pre-scaled) and value weights p * s^ (pre-scaled, pair order);
     // the cross-wave combine at the end reuses the key-weight space
     // (rows padded so that the 4 rows of a wave, which read different groups, hit different banks)
     typedef float KwT[NV][NGT][D + 4];
+    typedef _Float16 KaT[NKS][NGT][32][4][4];  // matrix path: [row set][group][A matrix][row][k]
     typedef _Float16 VwT[NV][4][NJ][32 + 8];
     typedef float PartT[NV][D + 2];
-    constexpr int KW_BYTES = 4 * (int)sizeof(KwT), PART_BYTES = 4 * (int)sizeof(PartT);
+    constexpr int KW_BYTES = 4 * (int)(MM ? sizeof(KaT) : sizeof(KwT)), PART_BYTES = 4 * (int)sizeof(PartT);
     constexpr int KP_BYTES = KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES;
     // with several heads the scaled queries live in LDS rather than in 8 registers per head
-    constexpr bool Q_LDS = NV >= 2;
+    constexpr bool Q_LDS = NV >= 2 || MM;
     typedef float QT[NV][D];
     __shared__ __attribute__((aligned(16))) char s_raw[KP_BYTES + 4 * sizeof(VwT) + (Q_LDS ? sizeof(QT) : 0)];
     KwT *s_kw = (KwT *)s_raw;
+    KaT *s_ka = (KaT *)s_raw;
     VwT *s_vw = (VwT *)(s_raw + KP_BYTES);
     PartT *s_part = (PartT *)s_raw;
     QT &s_q = *(QT *)(s_raw + KP_BYTES + 4 * sizeof(VwT));
@@ -212,6 +269,27 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
     if (split < a.n_splits) {
         // ------------------------------------------------------------ packed tokens
         const int gi = lane / LPG, li = lane % LPG;  // key-weight prep role
+        // matrix path: value accumulators [row set][channel] x 4 heads; the A matrices this lane
+        // prepares (first channel, 2^-bit of their two code positions); per head the exponent of
+        // the largest |q| and the power of two that scales its weights into fp16 range
+        float4_t accm[MM ? NVS : 1][CPL];
+        int kch[MM ? NPL : 1];
+        float kpw[MM ? NPL : 1][2];
+        int eq[MM ? NV : 1];
+        float qsc[MM ? NV : 1];
+        if constexpr (MM) {
+#pragma unroll
+            for (int x = 0; x < NVS; ++x)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) accm[x][c] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < NPL; ++e) {
+                const int n = li * NPL + e, ci = n / 2, p0 = 2 * (n % 2), p4 = (ci % CPB) * 4;
+                kch[e] = (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + p4 + p0;
+                kpw[e][0] = __builtin_ldexpf(1.0f, -BK * (p4 + p0));
+                kpw[e][1] = __builtin_ldexpf(1.0f, -BK * (p4 + p0 + 1));
+            }
+        }
         float qz[Q_LDS ? 1 : NV][CPP];  // q * sm_scale * log2(e) for the channels this lane prepares
         float pw[CPP];      // the code of channel c arrives as c * 2^((BK*c) mod 8 - 24); undo it in the weight
 #pragma unroll
@@ -219,7 +297,28 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
         // with few heads a second, pre-shifted copy of q saves a multiply per weight
         constexpr bool QK_COPY = NV == 1;
         float qk[QK_COPY ? NV : 1][CPP];
-        if constexpr (Q_LDS) {
+        if constexpr (MM) {
+            // scaled queries in the order the A matrices take their channels: matrix n, element k
+            for (int idx = tid; idx < NV * D; idx += 256) {
+                const int v = idx / D, pos = idx % D, n = pos / 4, k = pos % 4;
+                const int ci = n / 2, p = 2 * (n % 2) + k / 2;
+                const int ch = (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4 + p + (k % 2) * HALFK;
+                s_q[v][pos] = hbits(qptr(v)[ch]) * a.scale_log2e;
+            }
+            if constexpr ((2 * NV) % 4 != 0) {  // rows of the last set that no head uses stay zero
+                uint32_t *z = (uint32_t *)s_raw;
+                for (int idx = tid; idx < KW_BYTES / 4; idx += 256) z[idx] = 0;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const float mx = wave_max(fmaxf(fabsf(s_q[v][lane]), fabsf(s_q[v][lane + 64])));
+                int e = (int)((__float_as_uint(mx) >> 23) & 0xffu) - 126;  // 2^e > |q| of every channel
+                e = __builtin_amdgcn_readfirstlane(min(max(e, -40), 60));
+                eq[v] = e;
+                qsc[v] = __uint_as_float((uint32_t)(127 + 14 - e) << 23);
+            }
+        } else if constexpr (Q_LDS) {
             for (int idx = tid; idx < NV * D; idx += 256) s_q[idx / D][idx % D] = hbits(qptr(idx / D)[idx % D]) * a.scale_log2e;
             __syncthreads();
         } else {
@@ -251,7 +350,70 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             const int blk_in = tin / 32 + row;
             // ---- key weights for the tile's groups -> LDS
             float zs[NV];
-            {
+            float fac[MM ? NV : 1];  // matrix path: score = (sum of the head's two rows) * fac + zs
+            if constexpr (MM) {
+                const int Gidx = tile * NGT + gi;
+                const bool g_ok = Gidx * G < seqTq;
+                uint32_t meta[NLAY][NPL][4];  // in the A matrix's k order
+#pragma unroll
+                for (int y = 0; y < NLAY; ++y)
+#pragma unroll
+                    for (int e = 0; e < NPL; ++e) {
+                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + slice * a.st.k_meta) +
+                                             (int64_t)(tin / G + gi) * D + kch[e];
+                        uint32_t t0[2] = {0, 0}, t1[2] = {0, 0};
+                        if (g_ok) {
+                            VecLoad<2>::ld(mp, t0);
+                            VecLoad<2>::ld(mp + HALFK, t1);
+                        }
+                        meta[y][e][0] = t0[0];
+                        meta[y][e][2] = t0[1];
+                        meta[y][e][1] = t1[0];
+                        meta[y][e][3] = t1[1];
+                    }
+#pragma unroll
+                for (int y = 0; y < NLAY; ++y) {
+                    uint32_t hm = 0;
+#pragma unroll
+                    for (int e = 0; e < NPL; ++e)
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) hm = max(hm, meta[y][e][k] & 0x7fffu);
+                    hm = group_umax<LPG>(hm);
+                    const int es = max((int)(hm >> 10), 1) - 14;  // 2^es > every scale of the group
+                    const float sinv = __uint_as_float((uint32_t)(127 - es) << 23);
+                    float sh[NPL][4], zh[NPL][4];
+#pragma unroll
+                    for (int e = 0; e < NPL; ++e)
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            sh[e][k] = hbits(meta[y][e][k] & 0xffffu) * (kpw[e][k / 2] * sinv);
+                            zh[e][k] = hbits(meta[y][e][k] >> 16);
+                        }
+#pragma unroll
+                    for (int n = 0; n < NREP; ++n) {
+                        const int v = y * NREP + n;
+                        float zp = 0.f;
+#pragma unroll
+                        for (int e = 0; e < NPL; ++e) {
+                            const float4 q4 = *(const float4 *)&s_q[v][(li * NPL + e) * 4];
+                            const float qv[4] = {q4.x, q4.y, q4.z, q4.w};
+                            half4_t hi, lo;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const float w = qv[k] * sh[e][k] * qsc[v];  // |w| < 2^14
+                                zp = fmaf(qv[k], zh[e][k], zp);
+                                hi[k] = (_Float16)w;
+                                lo[k] = (_Float16)(w - (float)hi[k]);
+                            }
+                            *(half4_t *)&s_ka[wave][(2 * v) / 4][gi][li * NPL + e][(2 * v) % 4][0] = hi;
+                            *(half4_t *)&s_ka[wave][(2 * v) / 4][gi][li * NPL + e][(2 * v) % 4 + 1][0] = lo;
+                        }
+                        zs[v] = group_sum<LPG>(zp);
+                        // codes arrive as c 2^(bit-24): sum = true sum * 2^(-es - eq - 10)
+                        fac[v] = __uint_as_float((uint32_t)(127 + 10 + es + eq[v]) << 23);
+                    }
+                }
+            } else {
                 const int Gidx = tile * NGT + gi;
                 const bool g_ok = Gidx * G < seqTq;
                 uint32_t meta[NLAY][CPP];
@@ -358,17 +520,56 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             // Chains per score: low-half and high-half channels, and with several heads also even
             // and odd positions.  A head step then never reuses an accumulator within 8
             // instructions; at 4 the compiler pads every reuse with a wait state.
-            constexpr int NCHAIN = NV > 1 ? 2 : 1;
-            float sc[2][NV][NCHAIN], sch[2][NV][NCHAIN];
+            float tsum[2][NV];  // code part of the scores of this lane's two tokens
+            const int kg = (row * 32) / G;  // key group of this row inside the tile
+            if constexpr (MM) {
+                // the lanes of a token group are the lanes that prepared it (kg == gi); A matrix n
+                // sits in block n % NB of register pair n / NB
+                constexpr int NCHUNK = WK * 2 * CPB;
+                const int bx = (lane % (4 * NB)) >> 2, ri = lane & 3;
+                half4_t ka[NKS][AREG];
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+                for (int x = 0; x < NKS; ++x)
+#pragma unroll
+                    for (int r = 0; r < AREG; ++r) ka[x][r] = *(const half4_t *)&s_ka[wave][x][kg][r * NB + bx][ri][0];
+                float4_t ak[NKS][2];
+#pragma unroll
+                for (int x = 0; x < NKS; ++x) ak[x][0] = ak[x][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ci = 0; ci < NCHUNK; ++ci) {
+                    const int wi = ci / (2 * CPB), src = (ci / CPB) % 2, p4 = (ci % CPB) * 4;
+                    uint32_t c2[2][4];
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        const uint32_t x = src ? (kc[s2][wi] >> 8) : kc[s2][wi];
+#pragma unroll
+                        for (int p = 0; p < 4; ++p) c2[s2][p] = x & (MASKK << (BK * (p4 + p)));
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int n = 2 * ci + h;
+#pragma unroll
+                        for (int x = 0; x < NKS; ++x)
+#pragma unroll
+                            for (int s2 = 0; s2 < 2; ++s2)
+                                ak[x][s2] = mfma_rows<CBSZ>(ka[x][n / NB], codes4(c2[s2][2 * h], c2[s2][2 * h + 1]),
+                                                            ak[x][s2], n % NB);
+                    }
+                }
 #pragma unroll
                 for (int v = 0; v < NV; ++v)
 #pragma unroll
-                    for (int e = 0; e < NCHAIN; ++e) sc[s][v][e] = sch[s][v][e] = 0.f;
-            const int kg = (row * 32) / G;  // key group of this row inside the tile
-            {
-                constexpr int CPB = BYTEK / 4;            // chunks of 4 positions per byte
+                    for (int s2 = 0; s2 < 2; ++s2)
+                        tsum[s2][v] = (ak[(2 * v) / 4][s2][(2 * v) % 4] + ak[(2 * v) / 4][s2][(2 * v) % 4 + 1]) * fac[v];
+            } else {
+                constexpr int NCHAIN = NV > 1 ? 2 : 1;
+                float sc[2][NV][NCHAIN], sch[2][NV][NCHAIN];
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+#pragma unroll
+                        for (int e = 0; e < NCHAIN; ++e) sc[s][v][e] = sch[s][v][e] = 0.f;
                 constexpr int NCHUNK = WK * 2 * CPB;
                 constexpr int NSTEP = NCHUNK * NV;
                 constexpr int PF = NSTEP > 2 ? 2 : 1;
@@ -411,6 +612,14 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         if constexpr (NV > 1) __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        float t = sc[s2][v][0] + sch[s2][v][0];
+                        if constexpr (NCHAIN == 2) t += sc[s2][v][1] + sch[s2][v][1];
+                        tsum[s2][v] = t;
+                    }
             }
             if constexpr (!V_LOAD_EARLY) load_values();
             // ---- online softmax bookkeeping (log2 domain), value weights -> LDS
@@ -430,11 +639,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             float pr[2][NV];
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                float t0 = sc[0][v][0] + sch[0][v][0], t1 = sc[1][v][0] + sch[1][v][0];
-                if constexpr (NCHAIN == 2) {
-                    t0 += sc[0][v][1] + sch[0][v][1];
-                    t1 += sc[1][v][1] + sch[1][v][1];
-                }
+                const float t0 = tsum[0][v], t1 = tsum[1][v];
                 float u0 = row_ok ? t0 + zs[v] : -INFINITY;
                 float u1 = row_ok ? t1 + zs[v] : -INFINITY;
                 float tmax = wave_max(fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]));
@@ -443,7 +648,10 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     float alpha = exp2_le0(m_run[v] - m_new);  // m_run = -inf gives 0
                     l_run[v] *= alpha;
 #pragma unroll
-                    for (int c = 0; c < CPL; ++c) accv[v][c] *= alpha;
+                    for (int c = 0; c < CPL; ++c) {
+                        if constexpr (MM) accm[v / 4][c][v % 4] *= alpha;
+                        else accv[v][c] *= alpha;
+                    }
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) zacc[v][j] *= alpha;
                     m_run[v] = m_new;
@@ -472,7 +680,37 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             wave_lds_fence();
             // ---- P . V^ over the packed codes
             const int jl = (lane * CPL) / G;  // channel group of this lane's channels
-            {
+            if constexpr (MM) {
+                // A matrix of token quad qd (4 tokens in pair order, one row per head) sits in block
+                // qd % NB of register pair qd / NB; the blocks of a channel group share it
+                const int bx = (lane % (4 * NB)) >> 2, ri = lane & 3;
+                half4_t va[NVS][AREG];
+#pragma unroll
+                for (int x = 0; x < NVS; ++x)
+#pragma unroll
+                    for (int r = 0; r < AREG; ++r) {
+                        const int qd = r * NB + bx, kb = qd / 8, q8 = qd % 8;
+                        const int v = min(4 * x + ri, NV - 1);  // rows past the last head repeat it; nobody reads them
+                        va[x][r] = *(const half4_t *)&s_vw[wave][v][kb][jl][(q8 / QPW) * TPW + 4 * (q8 % QPW)];
+                    }
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int m = 0; m < WS; ++m)
+#pragma unroll
+                        for (int qq = 0; qq < QPW; ++qq) {
+                            const int qd = kb * 8 + m * QPW + qq;
+#pragma unroll
+                            for (int c = 0; c < CPL; ++c) {
+                                const int bit0 = BV * ((2 * qq) * CPL + c), bit1 = BV * ((2 * qq + 1) * CPL + c);
+                                const uint32_t x0 = (bit0 >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                                const uint32_t x1 = (bit1 >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                                const half4_t b = codes4(x0 & (MASKV << (bit0 & 7)), x1 & (MASKV << (bit1 & 7)));
+#pragma unroll
+                                for (int x = 0; x < NVS; ++x) accm[x][c] = mfma_rows<CBSZ>(va[x][qd / NB], b, accm[x][c], qd % NB);
+                            }
+                        }
+            } else {
                 constexpr int VCH = (TPW / 2) / 4;        // chunks of 4 token pairs per word
                 constexpr int NCHUNK = 4 * WS * VCH;
                 constexpr int NSTEP = NCHUNK * NV;
@@ -527,8 +765,10 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
             for (int j = 1; j < NJ; ++j) zsel = (jl == j) ? zj[j] : zsel;
 #pragma unroll
-            for (int c = 0; c < CPL; ++c)
+            for (int c = 0; c < CPL; ++c) {
+                if constexpr (MM) accv[v][c] = accm[v / 4][c][v % 4];
                 accv[v][c] = accv[v][c] * __builtin_ldexpf(1.0f, 18 - BV * c) + zsel;
+            }
         }
         __syncthreads();  // every wave is done with the key weights before their space is reused
 #pragma unroll
@@ -652,12 +892,24 @@ hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipSt
     XqDecodeArgs b = a;
     b.n_launch_z = pair_fused ? n_layers / 2 : n_layers;
     dim3 grid((unsigned)((a.n_splits + 1) * a.batch * a.n_kv_heads * b.n_launch_z));
+    constexpr bool HAS_MM = D == 128;  // the matrix path is built for head_dim 128
+    if (a.matrix && !HAS_MM) return hipErrorInvalidValue;
     if (pair_fused) {
         // 2 * NREP virtual heads must fit the LDS weight tables
         if constexpr (2 * NREP * (XQ_TILE_TOKENS / G) <= 16 && (D == 128 || NREP == 1)) {
-            xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(b);
+            if constexpr (HAS_MM) {
+                if (a.matrix) xq_decode_kernel<D, G, BK, BV, NREP, 2, false, true><<<grid, block, 0, s>>>(b);
+                else xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(b);
+            } else {
+                xq_decode_kernel<D, G, BK, BV, NREP, 2><<<grid, block, 0, s>>>(b);
+            }
         } else {
             return hipErrorInvalidValue;
+        }
+    } else if (a.matrix) {
+        if constexpr (HAS_MM) {
+            if (a.reuse_codes) xq_decode_kernel<D, G, BK, BV, NREP, 1, true, true><<<grid, block, 0, s>>>(b);
+            else xq_decode_kernel<D, G, BK, BV, NREP, 1, false, true><<<grid, block, 0, s>>>(b);
         }
     } else {
         if (a.reuse_codes) xq_decode_kernel<D, G, BK, BV, NREP, 1, true><<<grid, block, 0, s>>>(b);

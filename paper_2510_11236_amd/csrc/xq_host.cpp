@@ -594,7 +594,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
                         void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                         int32_t flags, void *hip_stream) {
     if (!range_ok(cache, layer0, n_layers) || !q_f16 || !out_f32 || !dev_workspace) return XQ_ERR_INVALID_ARG;
-    if (flags & ~XQ_DECODE_PAIR_FUSED) return XQ_ERR_INVALID_ARG;
+    if (flags & ~(XQ_DECODE_PAIR_FUSED | XQ_DECODE_VECTOR_ALU)) return XQ_ERR_INVALID_ARG;
     if (((uintptr_t)q_f16 & 3) || ((uintptr_t)out_f32 & 3) || ((uintptr_t)dev_workspace & 15)) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
     const int32_t *row = len_row(cache, layer0);
@@ -683,6 +683,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
         a.pg = cache->paging;
+        a.matrix = c.head_dim == 128 && !(flags & XQ_DECODE_VECTOR_ALU);
         if (!fused)
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;

@@ -136,6 +136,7 @@ struct XqDecodeArgs {
     int32_t rep, q_head0;  // query heads per kv head; first of them that this launch serves (it serves n_rep)
     int32_t reuse_codes;  // some layer of the launch reads another layer's codes (keep them in L2)
     int32_t pair_order;   // ... and the launch is a whole number of sharing groups of this many layers (0: not): deal their workgroups out side by side
+    int32_t matrix;       // multiply-adds on the 4x4x4 matrix instruction (head_dim 128) instead of the vector ALU
     XqPaging pg;
     int32_t seq_T[XQ_MAX_RAGGED];
 };

@@ -400,14 +400,14 @@ def test_determinism_and_error_codes(lib_):
                      "k_res": 56 * 256, "v_res": 56 * 256}[name]   # T_q = 2944, r = 56 tokens used
                 assert torch.equal(a[:, :n], b[:, :n]), (name, l)
     q = synth.queries(w).cuda()
-    for flags in (0, 1):
+    for flags in (0, 1, 2, 3):
         o1 = c1.decode_attention(q, 0.1, flags=flags)
         o2 = c1.decode_attention(q, 0.1, flags=flags)
         o3 = c2.decode_attention(q, 0.1, flags=flags)
         assert torch.equal(o1, o2) and torch.equal(o1, o3)
     # error paths of decode: bad flag, layers of different length, workspace too small
     with pytest.raises(XqError) as e:
-        c1.decode_attention(q, 0.1, flags=2)
+        c1.decode_attention(q, 0.1, flags=4)
     assert e.value.code == -1
     c1.append_token(Kd[:2, :, :, 0].contiguous(), Vd[:2, :, :, 0].contiguous(), layer0=0)
     with pytest.raises(XqError) as e:
