@@ -340,44 +340,114 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
         // (the layers of a group that run side by side start at the same tile: they read the same codes)
         const int lrot = (REUSE && a.pair_order) ? lz / a.pair_order : lz;
         const int rot = n_tiles > 0 ? (int)((bh * 37u + lrot * 11u) % (unsigned)n_tiles) : 0;
-        for (int it = wave; it < n_tiles; it += 4) {
-            const int tile = tile0 + (it + rot) % n_tiles;
-            const int blk = tile * 4 + row;
-            const bool row_ok = blk < n_blocks;
-            // where the tile's 128 tokens are stored: the sequence's own slice, or a page's
-            int tin;
-            const int64_t slice = xq_locate(a.pg, bi, hkv, a.n_kv_heads, tile * XQ_TILE_TOKENS, &tin);
-            const int blk_in = tin / 32 + row;
-            // ---- key weights for the tile's groups -> LDS
-            float zs[NV];
-            float fac[MM ? NV : 1];  // matrix path: score = (sum of the head's two rows) * fac + zs
+        // Register-resident inputs of a tile: this lane's two key rows (tokens r16 and r16 + 16 of
+        // its block), the value codes of the tile for its channels, the value metadata of its two
+        // tokens, and (matrix path) the key metadata of the A matrices it prepares, in their k order.
+        // The plain path loads them inside the tile's own iteration.  The matrix path spends less
+        // time per tile and keeps a tile's worth of loads in flight instead: each set is reloaded
+        // for the wave's next tile as soon as the current tile has consumed it.
+        uint32_t kc[2][WK];
+        uint32_t vc[4][WS];
+        uint32_t vm[NLAY][2][NJ];
+        uint32_t kmeta[MM ? NLAY : 1][MM ? NPL : 1][4];
+        struct TileAt {
+            int tile, tin;   // tile number; index of its first token inside the slice
+            int64_t slice;   // where its 128 tokens are stored: the sequence's own slice, or a page's
+        };
+        auto tile_at = [&](int it) {
+            TileAt t;
+            t.tile = tile0 + (it + rot) % n_tiles;
+            t.slice = xq_locate(a.pg, bi, hkv, a.n_kv_heads, t.tile * XQ_TILE_TOKENS, &t.tin);
+            return t;
+        };
+        auto load_kmeta = [&](const TileAt &t) {
             if constexpr (MM) {
-                const int Gidx = tile * NGT + gi;
-                const bool g_ok = Gidx * G < seqTq;
-                uint32_t meta[NLAY][NPL][4];  // in the A matrix's k order
+                const bool g_ok = (t.tile * NGT + gi) * G < seqTq;
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y)
 #pragma unroll
                     for (int e = 0; e < NPL; ++e) {
-                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + slice * a.st.k_meta) +
-                                             (int64_t)(tin / G + gi) * D + kch[e];
+                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + t.slice * a.st.k_meta) +
+                                             (int64_t)(t.tin / G + gi) * D + kch[e];
                         uint32_t t0[2] = {0, 0}, t1[2] = {0, 0};
                         if (g_ok) {
                             VecLoad<2>::ld(mp, t0);
                             VecLoad<2>::ld(mp + HALFK, t1);
                         }
-                        meta[y][e][0] = t0[0];
-                        meta[y][e][2] = t0[1];
-                        meta[y][e][1] = t1[0];
-                        meta[y][e][3] = t1[1];
+                        kmeta[y][e][0] = t0[0];
+                        kmeta[y][e][2] = t0[1];
+                        kmeta[y][e][1] = t1[0];
+                        kmeta[y][e][3] = t1[1];
                     }
+            }
+        };
+        auto load_kcodes = [&](const TileAt &t) {
+            const bool row_ok = t.tile * 4 + row < n_blocks;
+            const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
+                                                    t.slice * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
+                                 (int64_t)(t.tin / 32 + row) * 32 * WK;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
+                    else {
+#pragma unroll
+                        for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
+                    }
+                }
+        };
+        auto load_values = [&](const TileAt &t) {
+            const bool row_ok = t.tile * 4 + row < n_blocks;
+            const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
+                                                    t.slice * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                if (t.tile * 4 + kb < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)(t.tin / 32 + kb) * 64 * WS + lane * WS, vc[kb]);
+                else {
+#pragma unroll
+                    for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
+                }
+            }
+#pragma unroll
+            for (int y = 0; y < NLAY; ++y)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + t.slice * a.st.v_meta) +
+                                         ((int64_t)(t.tin / 32 + row) * 32 + r16 + 16 * s) * NJ;
+                    if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
+                    else {
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) vm[y][s][j] = 0;
+                    }
+                }
+        };
+        if constexpr (MM) {
+            if (wave < n_tiles) {
+                const TileAt t = tile_at(wave);
+                load_kmeta(t);
+                load_kcodes(t);
+                load_values(t);
+            }
+        }
+        for (int it = wave; it < n_tiles; it += 4) {
+            const TileAt cur = tile_at(it);
+            const bool more = it + 4 < n_tiles;
+            const TileAt nxt = (MM && more) ? tile_at(it + 4) : cur;
+            const int tile = cur.tile, tin = cur.tin;
+            const int64_t slice = cur.slice;
+            const bool row_ok = tile * 4 + row < n_blocks;
+            // ---- key weights for the tile's groups -> LDS
+            float zs[NV];
+            float fac[MM ? NV : 1];  // matrix path: score = (sum of the head's two rows) * fac + zs
+            if constexpr (MM) {
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y) {
                     uint32_t hm = 0;
 #pragma unroll
                     for (int e = 0; e < NPL; ++e)
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) hm = max(hm, meta[y][e][k] & 0x7fffu);
+                        for (int k = 0; k < 4; ++k) hm = max(hm, kmeta[y][e][k] & 0x7fffu);
                     hm = group_umax<LPG>(hm);
                     const int es = max((int)(hm >> 10), 1) - 14;  // 2^es > every scale of the group
                     const float sinv = __uint_as_float((uint32_t)(127 - es) << 23);
@@ -386,8 +456,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     for (int e = 0; e < NPL; ++e)
 #pragma unroll
                         for (int k = 0; k < 4; ++k) {
-                            sh[e][k] = hbits(meta[y][e][k] & 0xffffu) * (kpw[e][k / 2] * sinv);
-                            zh[e][k] = hbits(meta[y][e][k] >> 16);
+                            sh[e][k] = hbits(kmeta[y][e][k] & 0xffffu) * (kpw[e][k / 2] * sinv);
+                            zh[e][k] = hbits(kmeta[y][e][k] >> 16);
                         }
 #pragma unroll
                     for (int n = 0; n < NREP; ++n) {
@@ -413,6 +483,7 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         fac[v] = __uint_as_float((uint32_t)(127 + 10 + es + eq[v]) << 23);
                     }
                 }
+                if (more) load_kmeta(nxt);
             } else {
                 const int Gidx = tile * NGT + gi;
                 const bool g_ok = Gidx * G < seqTq;
@@ -463,58 +534,12 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     }
                 }
             }
-            // ---- this lane's two key rows (tokens r16 and r16 + 16 of block blk)
-            uint32_t kc[2][WK];
-            {
-                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
-                                                        slice * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
-                                     (int64_t)blk_in * 32 * WK;
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int ch = 0; ch < NCH; ++ch) {
-                        if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
-                        else {
-#pragma unroll
-                            for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
-                        }
-                    }
-            }
-            // ---- value codes of the tile for this lane's channels, value metadata of its two tokens.
-            // With one head the loads are issued here, ahead of the key phase; with several heads
-            // they are issued after it, which keeps 32+ registers free during the key loop (one
-            // more wave per SIMD) at the cost of latency that the other waves cover.
+            // ---- plain path: this tile's key rows now; its value inputs now with one head, and
+            // after the key phase with several, which keeps 32+ registers free during the key loop
+            // (one more wave per SIMD) at the cost of latency that the other waves cover
             constexpr bool V_LOAD_EARLY = NV == 1;
-            uint32_t vc[4][WS];
-            uint32_t vm[NLAY][2][NJ];
-            auto load_values = [&]() {
-                {
-                    const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
-                                                            slice * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
-#pragma unroll
-                    for (int kb = 0; kb < 4; ++kb) {
-                        const int b2 = tile * 4 + kb;
-                        if (b2 < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)(tin / 32 + kb) * 64 * WS + lane * WS, vc[kb]);
-                        else {
-#pragma unroll
-                            for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
-                        }
-                    }
-                }
-#pragma unroll
-                for (int y = 0; y < NLAY; ++y)
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + slice * a.st.v_meta) +
-                                             ((int64_t)blk_in * 32 + r16 + 16 * s) * NJ;
-                        if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
-                        else {
-#pragma unroll
-                            for (int j = 0; j < NJ; ++j) vm[y][s][j] = 0;
-                        }
-                    }
-            };
-            if constexpr (V_LOAD_EARLY) load_values();
+            if constexpr (!MM) load_kcodes(cur);
+            if constexpr (!MM && V_LOAD_EARLY) load_values(cur);
             wave_lds_fence();
             // ---- q . K^ over the packed codes
             // Chains per score: low-half and high-half channels, and with several heads also even
@@ -621,7 +646,11 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         tsum[s2][v] = t;
                     }
             }
-            if constexpr (!V_LOAD_EARLY) load_values();
+            if constexpr (MM) {
+                if (more) load_kcodes(nxt);
+            } else if constexpr (!V_LOAD_EARLY) {
+                load_values(cur);
+            }
             // ---- online softmax bookkeeping (log2 domain), value weights -> LDS
             // The value weights p * s^ travel as fp16.  A token whose largest value scale is
             // >= 2^9 raises the softmax reference by the excess exponent, which keeps every
@@ -642,9 +671,12 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 const float t0 = tsum[0][v], t1 = tsum[1][v];
                 float u0 = row_ok ? t0 + zs[v] : -INFINITY;
                 float u1 = row_ok ? t1 + zs[v] : -INFINITY;
-                float tmax = wave_max(fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]));
-                float m_new = fmaxf(m_run[v], tmax);
-                if (m_new > m_run[v]) {  // wave-uniform
+                // The running maximum only has to bound the scores: it moves when some token of the
+                // tile exceeds it (one compare and a wave-uniform branch, rarely taken after the
+                // first tiles), and only then is the tile's maximum reduced over the wave.
+                const float tl = fmaxf(u0 + eadd[v / NREP][0], u1 + eadd[v / NREP][1]);
+                if (__any(tl > m_run[v])) {
+                    const float m_new = fmaxf(m_run[v], wave_max(tl));
                     float alpha = exp2_le0(m_run[v] - m_new);  // m_run = -inf gives 0
                     l_run[v] *= alpha;
 #pragma unroll
@@ -656,8 +688,8 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     for (int j = 0; j < NJ; ++j) zacc[v][j] *= alpha;
                     m_run[v] = m_new;
                 }
-                pr[0][v] = exp2_le0(u0 - m_new);
-                pr[1][v] = exp2_le0(u1 - m_new);
+                pr[0][v] = exp2_le0(u0 - m_run[v]);
+                pr[1][v] = exp2_le0(u1 - m_run[v]);
                 l_run[v] += pr[0][v] + pr[1][v];
             }
 #pragma unroll
@@ -693,23 +725,27 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                         const int v = min(4 * x + ri, NV - 1);  // rows past the last head repeat it; nobody reads them
                         va[x][r] = *(const half4_t *)&s_vw[wave][v][kb][jl][(q8 / QPW) * TPW + 4 * (q8 % QPW)];
                     }
+                // step st = (token quad qd, channel c); the codes of a step are isolated one step ahead
+                // of the instruction that reads them (a freshly written operand would stall it)
+                auto vcodes = [&](int st) {
+                    const int qd = st / CPL, c = st % CPL, kb = qd / 8, m = (qd % 8) / QPW, qq = qd % QPW;
+                    const int bit0 = BV * ((2 * qq) * CPL + c), bit1 = BV * ((2 * qq + 1) * CPL + c);
+                    const uint32_t x0 = (bit0 >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                    const uint32_t x1 = (bit1 >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
+                    return codes4(x0 & (MASKV << (bit0 & 7)), x1 & (MASKV << (bit1 & 7)));
+                };
+                half4_t bn = vcodes(0);
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb)
+                for (int st = 0; st < 32 * CPL; ++st) {
+                    const int qd = st / CPL, c = st % CPL;
+                    const half4_t b = bn;
+                    if (st + 1 < 32 * CPL) bn = vcodes(st + 1);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int m = 0; m < WS; ++m)
-#pragma unroll
-                        for (int qq = 0; qq < QPW; ++qq) {
-                            const int qd = kb * 8 + m * QPW + qq;
-#pragma unroll
-                            for (int c = 0; c < CPL; ++c) {
-                                const int bit0 = BV * ((2 * qq) * CPL + c), bit1 = BV * ((2 * qq + 1) * CPL + c);
-                                const uint32_t x0 = (bit0 >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
-                                const uint32_t x1 = (bit1 >= 8) ? (vc[kb][m] >> 8) : vc[kb][m];
-                                const half4_t b = codes4(x0 & (MASKV << (bit0 & 7)), x1 & (MASKV << (bit1 & 7)));
-#pragma unroll
-                                for (int x = 0; x < NVS; ++x) accm[x][c] = mfma_rows<CBSZ>(va[x][qd / NB], b, accm[x][c], qd % NB);
-                            }
-                        }
+                    for (int x = 0; x < NVS; ++x) accm[x][c] = mfma_rows<CBSZ>(va[x][qd / NB], b, accm[x][c], qd % NB);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (more) load_values(nxt);
             } else {
                 constexpr int VCH = (TPW / 2) / 4;        // chunks of 4 token pairs per word
                 constexpr int NCHUNK = 4 * WS * VCH;
