@@ -147,8 +147,11 @@ __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp
 // weights are split into an fp16 high and low part (two rows) after a per-group power-of-two
 // scaling, which keeps ~22 bits of them for any input; value weights are the same fp16 numbers
 // as in the plain path.
+// (The one-head matrix kernel is held to 128 registers, 4 waves per SIMD: it needs 132 otherwise
+// and is 5 % faster with the fourth wave; the others spill when squeezed and keep their 3.)
 template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false, bool MM = false>
-__global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MM && NREP * NLAY == 1 ? 4 : 1, 8)))
+void xq_decode_kernel(XqDecodeArgs a) {
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane
     constexpr int NJ = D / G;             // value groups per token
@@ -305,10 +308,6 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                 const int ch = (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4 + p + (k % 2) * HALFK;
                 s_q[v][pos] = hbits(qptr(v)[ch]) * a.scale_log2e;
             }
-            if constexpr ((2 * NV) % 4 != 0) {  // rows of the last set that no head uses stay zero
-                uint32_t *z = (uint32_t *)s_raw;
-                for (int idx = tid; idx < KW_BYTES / 4; idx += 256) z[idx] = 0;
-            }
             __syncthreads();
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
@@ -354,9 +353,9 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
             int tile, tin;   // tile number; index of its first token inside the slice
             int64_t slice;   // where its 128 tokens are stored: the sequence's own slice, or a page's
         };
-        auto tile_at = [&](int it) {
+        auto tile_at = [&](int pos) {  // pos: position inside the split, rotation applied
             TileAt t;
-            t.tile = tile0 + (it + rot) % n_tiles;
+            t.tile = tile0 + pos;
             t.slice = xq_locate(a.pg, bi, hkv, a.n_kv_heads, t.tile * XQ_TILE_TOKENS, &t.tin);
             return t;
         };
@@ -422,18 +421,20 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
                     }
                 }
         };
+        int pos = n_tiles > 0 ? (wave + rot) % n_tiles : 0;  // advances by 4 and wraps; the wave's tiles are it = wave, wave + 4, ...
         if constexpr (MM) {
             if (wave < n_tiles) {
-                const TileAt t = tile_at(wave);
+                const TileAt t = tile_at(pos);
                 load_kmeta(t);
                 load_kcodes(t);
                 load_values(t);
             }
         }
         for (int it = wave; it < n_tiles; it += 4) {
-            const TileAt cur = tile_at(it);
-            const bool more = it + 4 < n_tiles;
-            const TileAt nxt = (MM && more) ? tile_at(it + 4) : cur;
+            const TileAt cur = tile_at(pos);
+            const bool more = it + 4 < n_tiles;  // then n_tiles > 4 and one subtraction wraps pos + 4
+            pos = pos + 4 >= n_tiles ? pos + 4 - n_tiles : pos + 4;
+            const TileAt nxt = (MM && more) ? tile_at(pos) : cur;
             const int tile = cur.tile, tin = cur.tin;
             const int64_t slice = cur.slice;
             const bool row_ok = tile * 4 + row < n_blocks;
@@ -556,7 +557,10 @@ __global__ __launch_bounds__(256) void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int x = 0; x < NKS; ++x)
 #pragma unroll
-                    for (int r = 0; r < AREG; ++r) ka[x][r] = *(const half4_t *)&s_ka[wave][x][kg][r * NB + bx][ri][0];
+                    for (int r = 0; r < AREG; ++r) {
+                        const int rr = min(4 * x + ri, 2 * NV - 1) - 4 * x;  // rows past the last head repeat it; nobody reads them
+                        ka[x][r] = *(const half4_t *)&s_ka[wave][x][kg][r * NB + bx][rr][0];
+                    }
                 float4_t ak[NKS][2];
 #pragma unroll
                 for (int x = 0; x < NKS; ++x) ak[x][0] = ak[x][1] = float4_t{0.f, 0.f, 0.f, 0.f};

@@ -26,11 +26,14 @@ def _run_prefill_case(tl, w, T, slices=None, fused_too=True, tps_list=(0,)):
     q = synth.queries(w).cuda()
     sigma = 1.0 / np.sqrt(w.head_dim)
     outs = []
+    # both kernel families: the matrix-instruction path (default at head_dim 128) and the
+    # vector-ALU path (flag 2; the only one at head_dim 64, where the flag changes nothing)
     for tps in tps_list:
         cache.set_tiles_per_split(tps)
-        outs.append(cache.decode_attention(q, sigma))
-        if fused_too:
-            outs.append(cache.decode_attention(q, sigma, flags=1))
+        for alu in (0, 2):
+            outs.append(cache.decode_attention(q, sigma, flags=alu))
+            if fused_too:
+                outs.append(cache.decode_attention(q, sigma, flags=1 | alu))
     torch.cuda.synchronize()
     if slices is None:
         slices = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
@@ -178,6 +181,37 @@ def test_append_from_empty_and_capacity(lib_):
     with pytest.raises(XqError) as e:
         cache.quantize_pack(torch.cat([Kd, Kd], 3), torch.cat([Vd, Vd], 3))
     assert e.value.code == -3
+    cache.close()
+
+
+@pytest.mark.parametrize("g,rep,vq", [(32, 1, 4), (64, 4, 0), (32, 2, 2)])
+def test_key_weight_range(lib_, g, rep, vq):
+    """Key scales and queries over the whole fp16 range: the matrix path carries the key weights
+    q * scale as two fp16 halves after a per-group power-of-two scaling, which must neither
+    overflow nor lose the small ones.  Heads: tiny keys with huge queries, huge keys with tiny
+    queries, outlier channels 300x the rest, a zero query."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[1], n_layers=4, batch=1, n_q_heads=4 * rep, n_kv_heads=4, group=g,
+                     kq=4, vq=vq, km=0, vm=0, eta1=1 / 6, eta2=0.045)
+    T = 1200
+    K, V = synth.kv_all(w, T)
+    q = synth.queries(w)
+    K[:, :, 0] = (K[:, :, 0].float() * 2e-3).half()
+    q[:, :, 0:rep] = (q[:, :, 0:rep].float() * 500).half()
+    K[:, :, 1] = (K[:, :, 1].float() * 400).half()
+    q[:, :, rep:2 * rep] = (q[:, :, rep:2 * rep].float() / 400).half()
+    K[:, :, 2, :, 7::16] = (K[:, :, 2, :, 7::16].float() * 300).half()
+    q[:, :, 2 * rep:3 * rep, 7::16] = (q[:, :, 2 * rep:3 * rep, 7::16].float() / 300).half()
+    q[:, :, 3 * rep] = 0
+    cache = tl.make_cache(w, max_tokens=T)
+    cache.quantize_pack(K.cuda(), V.cuda())
+    sigma = 1.0 / np.sqrt(w.head_dim)
+    outs = [cache.decode_attention(q.cuda(), sigma, flags=f) for f in (0, 1, 2, 3)]
+    for h in range(4):
+        st = tl.oracle_slice(w, K, V, 0, h)
+        ref = tl.oracle_attention(w, st, q, 0, h, sigma)
+        for o in outs:
+            tl.check_attention(o, w, ref, 0, h)
     cache.close()
 
 
