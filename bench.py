@@ -303,7 +303,7 @@ def main():
         "equivalent_bits": {"paper_definition": equivalent_bits(cfg), "with_metadata_and_ring": equivalent_bits(cfg, True, T0)},
     }
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file) and not args.page_tokens:
+    if os.path.exists(traffic_file) and not args.page_tokens and not args.vector_alu:
         try:
             prof = json.load(open(traffic_file))
             res["roofline"]["traffic"] = prof.get(f"{w.name}:{schedule}")
@@ -311,11 +311,13 @@ def main():
             if insts:
                 # second roof: vector-ALU issue.  Peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
                 # (one instruction per lane per cycle; packed-fp32 forms are not used); achieved = the launch's
-                # counted VALU instructions (SQ_INSTS_VALU, 64 lanes each) over the measured duration.
+                # counted VALU instructions (SQ_INSTS_VALU, 64 lanes each; the matrix instructions, which
+                # take an issue slot like any other, are among them) over the measured duration.
                 peak = 256 * 4 * 16 * 2.4e9
                 ach = insts * 64 / (decode_ms * 1e-3)
                 res["alu_issue"] = {"achieved": ach, "peak": peak, "unit": "lane-instructions/s", "frac": ach / peak,
-                                    "valu_wave_instructions_per_launch": insts}
+                                    "valu_wave_instructions_per_launch": insts,
+                                    "of_which_matrix_instructions": prof.get(f"{w.name}:{schedule}:mfma_wave_instructions")}
         except Exception:
             pass
     if not args.no_cpu_baseline:

@@ -8,7 +8,8 @@
 // halves of a register, where each half is read as an fp16 subnormal c * 2^(shift-24)
 // (the power of two is undone exactly in the uniform operand), and one FMA per code
 // (keys: fp32 weight x fp16 code, v_fma_mix) or one dot2 per pair (values: fp16 weights)
-// accumulates in fp32.  No MFMA: one query per head makes this a bandwidth-bound GEMV.
+// accumulates in fp32.  That is the vector-ALU family; with head_dim 128 the default family hands
+// the same masked codes, four at a time, to the 4x4x4 fp16 matrix instruction instead (MM below).
 //
 // Work split: one workgroup per (packed-token split, sequence, kv head, layer or layer pair),
 // plus one per (sequence, kv head, layer) for the fp16 ring, in a 1-D grid.  A workgroup has
