@@ -274,8 +274,8 @@ void xq_decode_kernel(XqDecodeArgs a) {
         // ------------------------------------------------------------ packed tokens
         const int gi = lane / LPG, li = lane % LPG;  // key-weight prep role
         // matrix path: value accumulators [row set][channel] x 4 heads; the A matrices this lane
-        // prepares (first channel, 2^-bit of their two code positions); per head the exponent of
-        // the largest |q| and the power of two that scales its weights into fp16 range
+        // prepares (first channel, 2^-bit of their two code positions); per head the exponent e of
+        // the largest |q| (the query table holds q 2^(14 - e)) and 2^(e - 14)
         float4_t accm[MM ? NVS : 1][CPL];
         int kch[MM ? NPL : 1];
         float kpw[MM ? NPL : 1][2];
@@ -316,8 +316,19 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 int e = (int)((__float_as_uint(mx) >> 23) & 0xffu) - 126;  // 2^e > |q| of every channel
                 e = __builtin_amdgcn_readfirstlane(min(max(e, -40), 60));
                 eq[v] = e;
-                qsc[v] = __uint_as_float((uint32_t)(127 + 14 - e) << 23);
+                qsc[v] = __uint_as_float((uint32_t)(127 - 14 + e) << 23);  // 2^(e - 14)
             }
+            // the table keeps q 2^(14 - e): weights come out in fp16 range without a multiply per
+            // channel, and the zero-point sum is scaled back once per head
+            __syncthreads();
+            for (int idx = tid; idx < NV * D; idx += 256) {
+                const int v = idx / D;
+                float f = 1.0f;
+#pragma unroll
+                for (int u = 0; u < NV; ++u) f = (u == v) ? __uint_as_float((uint32_t)(127 + 14 - eq[u]) << 23) : f;
+                s_q[v][idx % D] *= f;
+            }
+            __syncthreads();
         } else if constexpr (Q_LDS) {
             for (int idx = tid; idx < NV * D; idx += 256) s_q[idx / D][idx % D] = hbits(qptr(idx / D)[idx % D]) * a.scale_log2e;
             __syncthreads();
@@ -472,15 +483,15 @@ void xq_decode_kernel(XqDecodeArgs a) {
                             half4_t hi, lo;
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
-                                const float w = qv[k] * sh[e][k] * qsc[v];  // |w| < 2^14
+                                const float w = qv[k] * sh[e][k];  // |w| < 2^14
                                 zp = fmaf(qv[k], zh[e][k], zp);
                                 hi[k] = (_Float16)w;
-                                lo[k] = (_Float16)(w - (float)hi[k]);
+                                lo[k] = (_Float16)__builtin_fmaf(qv[k], sh[e][k], -(float)hi[k]);  // exact product - hi
                             }
                             *(half4_t *)&s_ka[wave][(2 * v) / 4][gi][li * NPL + e][(2 * v) % 4][0] = hi;
                             *(half4_t *)&s_ka[wave][(2 * v) / 4][gi][li * NPL + e][(2 * v) % 4 + 1][0] = lo;
                         }
-                        zs[v] = group_sum<LPG>(zp);
+                        zs[v] = group_sum<LPG>(zp) * qsc[v];
                         // codes arrive as c 2^(bit-24): sum = true sum * 2^(-es - eq - 10)
                         fac[v] = __uint_as_float((uint32_t)(127 + 10 + es + eq[v]) << 23);
                     }
@@ -544,9 +555,6 @@ void xq_decode_kernel(XqDecodeArgs a) {
             if constexpr (!MM && V_LOAD_EARLY) load_values(cur);
             wave_lds_fence();
             // ---- q . K^ over the packed codes
-            // Chains per score: low-half and high-half channels, and with several heads also even
-            // and odd positions.  A head step then never reuses an accumulator within 8
-            // instructions; at 4 the compiler pads every reuse with a wait state.
             float tsum[2][NV];  // code part of the scores of this lane's two tokens
             const int kg = (row * 32) / G;  // key group of this row inside the tile
             if constexpr (MM) {
@@ -592,6 +600,9 @@ void xq_decode_kernel(XqDecodeArgs a) {
                     for (int s2 = 0; s2 < 2; ++s2)
                         tsum[s2][v] = (ak[(2 * v) / 4][s2][(2 * v) % 4] + ak[(2 * v) / 4][s2][(2 * v) % 4 + 1]) * fac[v];
             } else {
+                // Chains per score: low-half and high-half channels, and with several heads also even
+                // and odd positions.  A head step then never reuses an accumulator within 8
+                // instructions; at 4 the compiler pads every reuse with a wait state.
                 constexpr int NCHAIN = NV > 1 ? 2 : 1;
                 float sc[2][NV][NCHAIN], sch[2][NV][NCHAIN];
 #pragma unroll
@@ -620,11 +631,10 @@ void xq_decode_kernel(XqDecodeArgs a) {
                     uint32_t c2[2][4];
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
-                            const uint32_t x = src ? (kc[s2][wi] >> 8) : kc[s2][wi];
+                        const uint32_t x = src ? (kc[s2][wi] >> 8) : kc[s2][wi];
 #pragma unroll
-                            for (int p = 0; p < 4; ++p)
-                                c2[s2][p] = x & (MASKK << (BK * (p4 + p)));
-                        }
+                        for (int p = 0; p < 4; ++p) c2[s2][p] = x & (MASKK << (BK * (p4 + p)));
+                    }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
                         const int st = ci * NV + v;
