@@ -173,7 +173,14 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 // workgroups finish together) plus a fifth of a workgroup of ragged tail.  The constants are fitted to
 // sweeps of n on the 4k, 16k, 32k and 256k configurations, all layers per call and one layer per
 // call.  The plan minimises that over n, with at most XQ_MAX_SPLITS splits.
-void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_splits, int *tiles_per_split) {
+// Workgroups of the decode kernel that one CU holds at a time: set by the registers of the
+// kernel variant (nv = query heads per kv head in the pass, times 2 when a pair shares a workgroup).
+int decode_wgs_per_cu(bool matrix, int nv) {
+    if (matrix) return nv == 1 ? 4 : (nv <= 4 ? 3 : 2);
+    return nv <= 2 ? 4 : (nv <= 4 ? 3 : 2);
+}
+
+void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int slots, int *n_splits, int *tiles_per_split) {
     int tiles = (Tq + XQ_TILE_TOKENS - 1) / XQ_TILE_TOKENS;
     if (tiles == 0) {
         *n_splits = 0;
@@ -194,7 +201,7 @@ void plan_splits(const xq_cache *cache, int Tq, int64_t work_items, int *n_split
         tps = tiles;
         for (int n = 1; n <= most; ++n) {
             const int t = (tiles + n - 1) / n;
-            const double fill = (double)work_items * ((tiles + t - 1) / t) / 1024.0;
+            const double fill = (double)work_items * ((tiles + t - 1) / t) / slots;
             // few rounds come in whole numbers (equal workgroups finish together); many rounds even out
             const double whole = ceil(fill), blend = fill < 8.0 ? 1.0 - fill / 8.0 : 0.0;
             const double rounds = fill <= 1.0 ? 1.0 : fill + (whole - fill) * blend;
@@ -653,8 +660,14 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         work_items += (int64_t)(fused ? (e - l) / 2 : e - l) * c.batch * c.n_kv_heads;
         l = e;
     }
+    // workgroup slots of the chip for the least resident kernel variant of the call
+    const bool matrix = c.head_dim == 128 && !(flags & XQ_DECODE_VECTOR_ALU);
+    int wgs_per_cu = 4;
+    for (int ri = 0; ri < n_runs; ++ri)
+        for (int i = 0; i < n_parts; ++i)
+            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(matrix, parts[i] * (runs[ri].fused ? 2 : 1)));
     int n_splits, tps;
-    plan_splits(cache, Tq, work_items, &n_splits, &tps);
+    plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &n_splits, &tps);
     if (workspace_floats(c, n_layers, n_splits) * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
     const int64_t per_layer_q = (int64_t)c.batch * c.n_q_heads * c.head_dim;
     const int64_t per_layer_ws = (int64_t)c.batch * c.n_q_heads * (n_splits + 1) * (c.head_dim + 2);
@@ -683,7 +696,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
         a.pg = cache->paging;
-        a.matrix = c.head_dim == 128 && !(flags & XQ_DECODE_VECTOR_ALU);
+        a.matrix = matrix;
         if (!fused)
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;

@@ -80,9 +80,11 @@ def test_random_config(seed):
         cache.append_token(Kd[:, :, :, t].contiguous(), Vd[:, :, :, t].contiguous())
     q = synth.queries(w).cuda()
     sigma = 1.0 / np.sqrt(w.head_dim)
-    outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1)]
+    # flag 1: pairs share a workgroup; flag 2: the vector-ALU kernels instead of the matrix-instruction ones
+    outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1),
+            cache.decode_attention(q, sigma, flags=2 + (seed // 2) % 2)]
     cache.set_tiles_per_split(1 + seed % 3)
-    outs.append(cache.decode_attention(q, sigma, flags=seed % 2))
+    outs.append(cache.decode_attention(q, sigma, flags=seed % 4))
     torch.cuda.synchronize()
     worst = 0.0
     for bi in range(w.batch):
