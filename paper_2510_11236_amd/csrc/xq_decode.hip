@@ -148,10 +148,12 @@ __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp
 // weights are split into an fp16 high and low part (two rows) after a per-group power-of-two
 // scaling, which keeps ~22 bits of them for any input; value weights are the same fp16 numbers
 // as in the plain path.
-// (The one-head matrix kernel is held to 128 registers, 4 waves per SIMD: it needs 132 otherwise
-// and is 5 % faster with the fourth wave; the others spill when squeezed and keep their 3.)
+// (Held to 128 registers, 4 waves per SIMD, where that costs no spill: the one-head matrix kernel
+// and the four-head one at g = 64 unless keys and values are both 2-bit; +5 % each.  The others
+// spill when squeezed and keep their 3 waves.)
 template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false, bool MM = false>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MM && NREP * NLAY == 1 ? 4 : 1, 8)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(
+    MM && (NREP * NLAY == 1 || (NREP == 4 && NLAY == 1 && G == 64 && BK + BV < 4)) ? 4 : 1, 8)))
 void xq_decode_kernel(XqDecodeArgs a) {
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane

@@ -174,9 +174,13 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 // sweeps of n on the 4k, 16k, 32k and 256k configurations, all layers per call and one layer per
 // call.  The plan minimises that over n, with at most XQ_MAX_SPLITS splits.
 // Workgroups of the decode kernel that one CU holds at a time: set by the registers of the
-// kernel variant (nv = query heads per kv head in the pass, times 2 when a pair shares a workgroup).
-int decode_wgs_per_cu(bool matrix, int nv) {
-    if (matrix) return nv == 1 ? 4 : (nv <= 4 ? 3 : 2);
+// kernel variant (n_rep query heads per kv head in the pass; a fused pair doubles the heads).
+int decode_wgs_per_cu(bool matrix, int n_rep, bool fused, int g, int bk, int bv) {
+    const int nv = n_rep * (fused ? 2 : 1);
+    if (matrix) {
+        if (nv == 1 || (n_rep == 4 && !fused && g == 64 && bk + bv < 4)) return 4;
+        return nv <= 4 ? 3 : 2;
+    }
     return nv <= 2 ? 4 : (nv <= 4 ? 3 : 2);
 }
 
@@ -665,7 +669,8 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
     int wgs_per_cu = 4;
     for (int ri = 0; ri < n_runs; ++ri)
         for (int i = 0; i < n_parts; ++i)
-            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(matrix, parts[i] * (runs[ri].fused ? 2 : 1)));
+            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(matrix, parts[i], runs[ri].fused != 0, c.group,
+                                                                cache->layers[runs[ri].l].bk, cache->layers[runs[ri].l].bv));
     int n_splits, tps;
     plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &n_splits, &tps);
     if (workspace_floats(c, n_layers, n_splits) * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
