@@ -148,12 +148,12 @@ __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp
 // weights are split into an fp16 high and low part (two rows) after a per-group power-of-two
 // scaling, which keeps ~22 bits of them for any input; value weights are the same fp16 numbers
 // as in the plain path.
-// (Held to 128 registers, 4 waves per SIMD, where that costs no spill: the one-head matrix kernel
-// and the four-head one at g = 64 unless keys and values are both 2-bit; +5 % each.  The others
-// spill when squeezed and keep their 3 waves.)
+// (Held to 128 registers, 4 waves per SIMD, where that costs no spill: the one- and two-head matrix
+// kernels and the four-head one at g = 64 unless keys and values are both 2-bit; +2 to 5 %.  The
+// others spill when squeezed and keep their 3 or 2 waves.)
 template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false, bool MM = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(
-    MM && (NREP * NLAY == 1 || (NREP == 4 && NLAY == 1 && G == 64 && BK + BV < 4)) ? 4 : 1, 8)))
+    MM && (NREP * NLAY <= 2 || (NREP == 4 && NLAY == 1 && G == 64 && BK + BV < 4)) ? 4 : 1, 8)))
 void xq_decode_kernel(XqDecodeArgs a) {
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane
@@ -435,11 +435,14 @@ void xq_decode_kernel(XqDecodeArgs a) {
                     }
                 }
         };
+        // (two heads at g = 32: the 16 registers of key metadata are loaded at the top of their own
+        // tile instead, which lets the kernel fit 128 registers, 4 waves per SIMD: +2.5 %)
+        constexpr bool PIPE_KMETA = !(NV == 2 && G == 32);
         int pos = n_tiles > 0 ? (wave + rot) % n_tiles : 0;  // advances by 4 and wraps; the wave's tiles are it = wave, wave + 4, ...
         if constexpr (MM) {
             if (wave < n_tiles) {
                 const TileAt t = tile_at(pos);
-                load_kmeta(t);
+                if constexpr (PIPE_KMETA) load_kmeta(t);
                 load_kcodes(t);
                 load_values(t);
             }
@@ -456,6 +459,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
             float zs[NV];
             float fac[MM ? NV : 1];  // matrix path: score = (sum of the head's two rows) * fac + zs
             if constexpr (MM) {
+                if constexpr (!PIPE_KMETA) load_kmeta(cur);
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y) {
                     uint32_t hm = 0;
@@ -498,7 +502,9 @@ void xq_decode_kernel(XqDecodeArgs a) {
                         fac[v] = __uint_as_float((uint32_t)(127 + 10 + es + eq[v]) << 23);
                     }
                 }
-                if (more) load_kmeta(nxt);
+                if constexpr (PIPE_KMETA) {
+                    if (more) load_kmeta(nxt);
+                }
             } else {
                 const int Gidx = tile * NGT + gi;
                 const bool g_ok = Gidx * G < seqTq;

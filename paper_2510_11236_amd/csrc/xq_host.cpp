@@ -178,7 +178,7 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 int decode_wgs_per_cu(bool matrix, int n_rep, bool fused, int g, int bk, int bv) {
     const int nv = n_rep * (fused ? 2 : 1);
     if (matrix) {
-        if (nv == 1 || (n_rep == 4 && !fused && g == 64 && bk + bv < 4)) return 4;
+        if (nv <= 2 || (n_rep == 4 && !fused && g == 64 && bk + bv < 4)) return 4;
         return nv <= 4 ? 3 : 2;
     }
     return nv <= 2 ? 4 : (nv <= 4 ? 3 : 2);
