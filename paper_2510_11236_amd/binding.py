@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libxq.so")
 _LIB = None
 
 XQ_DECODE_PAIR_FUSED = 1
+XQ_DECODE_VECTOR_ALU = 2
 
 
 class XqError(RuntimeError):

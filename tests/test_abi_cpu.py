@@ -35,6 +35,12 @@ def test_exports_every_declared_symbol(xq):
         assert hasattr(L, n), n
 
 
+def test_flag_constants_match_header(xq):
+    hdr = open(os.path.join(ROOT, "include", "xq.h")).read()
+    for name in ("XQ_DECODE_PAIR_FUSED", "XQ_DECODE_VECTOR_ALU"):
+        assert int(re.search(r"#define\s+%s\s+(\d+)" % name, hdr).group(1)) == getattr(xq, name)
+
+
 def _cfg(xq, **kw):
     base = dict(n_layers=32, batch=4, n_q_heads=32, n_kv_heads=32, head_dim=128, group=32, residual=128,
                 max_tokens=32768 + 1, kq=32, vq=32, km=0, vm=0, eta1=1 / 6, eta2=0.045)
