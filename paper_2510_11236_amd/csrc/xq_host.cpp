@@ -641,10 +641,11 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
     // runs of layers with one (bk, bv) and one fusion mode share a launch
     struct Run {
         int l, e, fused;
+        int n_splits, tps;  // each run is a launch of its own and gets its own split plan
+        int64_t ws_off;     // where its partials start in the workspace, in floats
     };
     Run runs[XQ_MAX_LAYERS];
     int n_runs = 0;
-    int64_t work_items = 0;  // (layer or pair, sequence, kv head) slices = workgroups per split
     for (int l = layer0; l < layer0 + n_layers;) {
         const XqLayerDesc &d0 = cache->layers[l];
         const int fused = fuse_mode(l);
@@ -660,24 +661,29 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
                 e += 1;
             }
         }
-        runs[n_runs++] = Run{l, e, fused};
-        work_items += (int64_t)(fused ? (e - l) / 2 : e - l) * c.batch * c.n_kv_heads;
+        runs[n_runs++] = Run{l, e, fused, 0, 0, 0};
         l = e;
     }
-    // workgroup slots of the chip for the least resident kernel variant of the call
     const bool matrix = c.head_dim == 128 && !(flags & XQ_DECODE_VECTOR_ALU);
-    int wgs_per_cu = 4;
-    for (int ri = 0; ri < n_runs; ++ri)
+    int64_t ws_floats = 0;
+    for (int ri = 0; ri < n_runs; ++ri) {
+        Run &r = runs[ri];
+        // (layer or pair, sequence, kv head) slices = workgroups per split; workgroup slots of the
+        // chip for the least resident kernel variant among the run's passes
+        const int64_t work_items = (int64_t)(r.fused ? (r.e - r.l) / 2 : r.e - r.l) * c.batch * c.n_kv_heads;
+        int wgs_per_cu = 4;
         for (int i = 0; i < n_parts; ++i)
-            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(matrix, parts[i], runs[ri].fused != 0, c.group,
-                                                                cache->layers[runs[ri].l].bk, cache->layers[runs[ri].l].bv));
-    int n_splits, tps;
-    plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &n_splits, &tps);
-    if (workspace_floats(c, n_layers, n_splits) * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
+            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(matrix, parts[i], r.fused != 0, c.group,
+                                                                cache->layers[r.l].bk, cache->layers[r.l].bv));
+        plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &r.n_splits, &r.tps);
+        r.ws_off = ws_floats;
+        ws_floats += (int64_t)workspace_floats(c, r.e - r.l, r.n_splits);
+    }
+    if ((size_t)ws_floats * sizeof(float) > workspace_bytes) return XQ_ERR_CAPACITY;
     const int64_t per_layer_q = (int64_t)c.batch * c.n_q_heads * c.head_dim;
-    const int64_t per_layer_ws = (int64_t)c.batch * c.n_q_heads * (n_splits + 1) * (c.head_dim + 2);
     for (int ri = 0; ri < n_runs; ++ri) {
         const int l = runs[ri].l, e = runs[ri].e, fused = runs[ri].fused;
+        const int n_splits = runs[ri].n_splits, tps = runs[ri].tps;
         const XqLayerDesc &d0 = cache->layers[l];
         XqDecodeArgs a;
         memset(&a, 0, sizeof(a));
@@ -698,7 +704,7 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         a.tiles_per_split = tps;
         a.q = (const uint16_t *)q_f16 + (int64_t)(l - layer0) * per_layer_q;
         a.out = (float *)out_f32 + (int64_t)(l - layer0) * per_layer_q;
-        a.ws = (float *)dev_workspace + (int64_t)(l - layer0) * per_layer_ws;
+        a.ws = (float *)dev_workspace + runs[ri].ws_off;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
         a.pg = cache->paging;
         a.matrix = matrix;
