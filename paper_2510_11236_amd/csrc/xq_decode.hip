@@ -189,7 +189,10 @@ void xq_decode_kernel(XqDecodeArgs a) {
     // (rows padded so that the 4 rows of a wave, which read different groups, hit different banks)
     typedef float KwT[NV][NGT][D + 4];
     typedef _Float16 KaT[NKS][NGT][32][4][4];  // matrix path: [row set][group][A matrix][row][k]
-    typedef _Float16 VwT[NV][4][NJ][32 + 8];
+    // (value-weight rows: padded by 8 halves against bank conflicts of the vector path's 16-byte
+    // reads; the matrix path reads 8 bytes per lane from a few broadcast addresses and goes without,
+    // which is what lets three workgroups of the four-head g = 32 kernel share a CU's LDS)
+    typedef _Float16 VwT[NV][4][NJ][32 + (MM ? 0 : 8)];
     typedef float PartT[NV][D + 2];
     constexpr int KW_BYTES = 4 * (int)(MM ? sizeof(KaT) : sizeof(KwT)), PART_BYTES = 4 * (int)sizeof(PartT);
     constexpr int KP_BYTES = KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES;

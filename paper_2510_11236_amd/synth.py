@@ -60,6 +60,8 @@ def workloads():
         # scaling checks on the 7B shape with all pairs shared: one very long sequence; a large batch
         Workload("long_7b_256k_b1_shared", 32, 1, 32, 32, 128, 262144, 32, 128, 32, 32, 0, 0, 1.0 / 6.0, 0.045, 6),
         Workload("wide_7b_32k_b16_shared", 32, 16, 32, 32, 128, 32768, 32, 128, 32, 32, 0, 0, 1.0 / 6.0, 0.045, 7),
+        # the GQA shape of cfg3 at the paper's group size 32, 2-bit keys and values, all pairs shared
+        Workload("gqa8b_32k_b8_k2v2_g32_shared", 32, 8, 32, 8, 128, 32768, 32, 128, 32, 32, 0, 0, 1.0 / 6.0, 0.045, 8),
     ]
 
 

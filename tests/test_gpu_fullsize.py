@@ -188,6 +188,15 @@ def test_cfg3_full_size_gqa(tl):
     print("cfg3 full size worst attention error", worst)
 
 
+def test_gqa_group32_full_size(tl):
+    """The GQA shape at the paper's group size 32 with 2-bit keys and values (four query heads per
+    kv head in one workgroup, four key groups per tile)."""
+    w = synth.workloads()[8]
+    worst = _run_full(tl, w, n_append=1, check_steps={1}, sample_pairs={0, 15},
+                      sample_bh=[(0, 0), (7, 7), (3, 5)])
+    print("GQA g=32 full size worst attention error", worst)
+
+
 def test_cfg1_full_size_unshared(tl):
     w = synth.workloads()[1]
     worst = _run_full(tl, w, n_append=1, check_steps={1}, sample_pairs={0, 7, 15},
