@@ -26,6 +26,7 @@ def _run_prefill_case(tl, w, T, slices=None, fused_too=True, tps_list=(0,)):
     q = synth.queries(w).cuda()
     sigma = 1.0 / np.sqrt(w.head_dim)
     outs = []
+    # tiles per split: 0 = the library's plan; 4096 = one split; small values = many splits
     # both kernel families: the matrix-instruction path (default at head_dim 128) and the
     # vector-ALU path (flag 2; the only one at head_dim 64, where the flag changes nothing)
     for tps in tps_list:
@@ -51,7 +52,7 @@ def _run_prefill_case(tl, w, T, slices=None, fused_too=True, tps_list=(0,)):
 
 def test_cfg0_tiny_pair(lib_):
     w = synth.workloads()[0]
-    worst = _run_prefill_case(lib_, w, w.context, tps_list=(0, 1, 2))
+    worst = _run_prefill_case(lib_, w, w.context, tps_list=(0, 1, 2, 4096))
     print("cfg0 worst attention error", worst)
 
 
@@ -74,7 +75,7 @@ def test_d128_variants(lib_, g, R, kq, vq, km, vm, rep):
     base = synth.workloads()[1]
     w = synth.scaled(base, n_layers=4, batch=2, n_q_heads=2 * rep, n_kv_heads=2, group=g, residual=R,
                      kq=kq, vq=vq, km=km, vm=vm, eta1=1 / 6, eta2=0.045, seed=11 + g + rep)
-    worst = _run_prefill_case(lib_, w, 1000, tps_list=(0, 1))
+    worst = _run_prefill_case(lib_, w, 1000, tps_list=(0, 1, 4096))
     print("variant worst attention error", worst)
 
 
@@ -86,7 +87,7 @@ def test_query_heads_per_kv_head(lib_, D, g, rep, km):
     base = synth.workloads()[1 if D == 128 else 0]
     w = synth.scaled(base, n_layers=4, batch=2, n_q_heads=2 * rep, n_kv_heads=2, group=g, residual=2 * g,
                      kq=4, vq=4, km=km, vm=km, eta1=1 / 6, eta2=0.045, seed=50 + rep)
-    worst = _run_prefill_case(lib_, w, 700, tps_list=(0, 2))
+    worst = _run_prefill_case(lib_, w, 700, tps_list=(0, 2, 4096))
     print("rep", rep, "worst attention error", worst)
 
 

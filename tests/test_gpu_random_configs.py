@@ -85,6 +85,8 @@ def test_random_config(seed):
             cache.decode_attention(q, sigma, flags=2 + (seed // 2) % 2)]
     cache.set_tiles_per_split(1 + seed % 3)
     outs.append(cache.decode_attention(q, sigma, flags=seed % 4))
+    cache.set_tiles_per_split(4096)       # one split
+    outs.append(cache.decode_attention(q, sigma, flags=(seed // 3) % 4))
     torch.cuda.synchronize()
     worst = 0.0
     for bi in range(w.batch):
