@@ -288,7 +288,9 @@ def main():
         "config": {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "context": T0, "group": w.group,
                    "residual": w.residual, "kq": w.kq, "vq": w.vq, "km": w.km, "vm": w.vm,
-                   "schedule": schedule, "page_tokens": args.page_tokens, "step": "append 1 token/sequence + decode attention, all layers in one call"},
+                   "schedule": schedule,
+                   "decode_kernels": "vector_alu" if (args.vector_alu or w.head_dim != 128) else "matrix_4x4x4_f16",
+                   "page_tokens": args.page_tokens, "step": "append 1 token/sequence + decode attention, all layers in one call"},
         "roofline": {"bound": "hbm", "kernel": "xq_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms},
