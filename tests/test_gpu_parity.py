@@ -115,11 +115,17 @@ def test_peaked_attention(lib_):
     cache.close()
 
 
-def test_append_equals_prefill(lib_):
+@pytest.mark.parametrize("D", [64, 128])
+def test_append_equals_prefill(lib_, D):
     """prefill(T0) + n appends == prefill(T0 + n): stored bytes bit for bit and attention,
-    across three ring flushes; checked against the oracle on the full history at several steps."""
+    across three ring flushes; checked against the oracle on the full history at several steps.
+    D = 128: four query heads per kv head, a shared pair (the matrix-instruction kernels)."""
     tl = lib_
-    w = synth.scaled(synth.workloads()[0], batch=2, n_q_heads=2, n_kv_heads=2, residual=64)
+    if D == 64:
+        w = synth.scaled(synth.workloads()[0], batch=2, n_q_heads=2, n_kv_heads=2, residual=64)
+    else:
+        w = synth.scaled(synth.workloads()[1], n_layers=2, batch=2, n_q_heads=8, n_kv_heads=2, residual=64,
+                         km=0, vm=0, eta1=1 / 6, eta2=0.045)
     T0, n = 150, 110
     K, V = synth.kv_all(w, T0 + n)
     Kd, Vd = K.cuda(), V.cuda()
@@ -146,8 +152,8 @@ def test_append_equals_prefill(lib_):
         for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
             a, b = cache.region(l, name), fresh.region(l, name)
             if a is not None:
-                used = {"k_codes": Tq * 64 * 2 // 8, "v_codes": Tq * 64 * 2 // 8, "k_meta": (Tq // 32) * 64 * 4,
-                        "v_meta": Tq * 2 * 4}[name]
+                used = {"k_codes": Tq * D * 2 // 8, "v_codes": Tq * D * 2 // 8, "k_meta": (Tq // 32) * D * 4,
+                        "v_meta": Tq * (D // 32) * 4}[name]
                 assert torch.equal(a[:, :used], b[:, :used]), (l, name)
     assert torch.equal(cache.decode_attention(q, sigma), fresh.decode_attention(q, sigma))
     cache.close()
