@@ -192,6 +192,23 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
                         void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                         int32_t flags, void *hip_stream);
 
+/* For callers that cannot allocate device memory or may not pass a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same call as
+ * xq_decode_attention, same kernels and same results, with the split partials kept in a device
+ * array of XQ_STATIC_SCRATCH_BYTES that is part of the library's code object instead of a caller
+ * workspace.  Each GPU the library runs on holds its own copy of that array until the process
+ * ends.  The call allocates and frees nothing and clears nothing (every partial a merge reads was
+ * written by the same call).  XQ_ERR_CAPACITY when the call's partials,
+ *   sum over its launches of layers * batch * n_q_heads * (splits + 1) * (head_dim + 2) * 4 bytes
+ * (splits <= 64, chosen by the library from the lengths), exceed XQ_STATIC_SCRATCH_BYTES: call it
+ * on fewer layers at a time, or use xq_decode_attention.  All calls on one GPU share the array:
+ * two calls that overlap in time on one GPU (different streams, different threads or different
+ * caches) race; calls on one stream are safe.  The array's address on a device is looked up once,
+ * in xq_cache_create on that device or else in the first call there. */
+#define XQ_STATIC_SCRATCH_BYTES (64u << 20)
+int xq_decode_attention_static(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
+                               void *out_f32, float sm_scale, int32_t flags, void *hip_stream);
+
 /* Test/debug: expands a layer's stored codes to one byte per element,
  * dev_codes_u8: device [batch][n_kv_heads][T_q][D].  XQ_ERR_STATE if the layer stores none or
  * its sequences differ in length. */

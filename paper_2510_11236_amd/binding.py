@@ -57,6 +57,8 @@ def lib():
         L.xq_cache_free_pages.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xq_append_token.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         L.xq_decode_attention.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, vp, C.c_size_t, C.c_int32, vp]
+        L.xq_decode_attention_static.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, C.c_int32, vp]
+        L.xq_decode_attention_static.restype = C.c_int
         L.xq_unpack_codes.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
         L.xq_code_delta_histogram.restype = C.c_int
         L.xq_code_delta_histogram.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
@@ -205,6 +207,16 @@ class XqCache:
                                          C.c_void_p(out.data_ptr()), float(sm_scale),
                                          C.c_void_p(self.workspace.data_ptr()), self.workspace.numel(), int(flags),
                                          _stream()), "xq_decode_attention")
+        return out
+
+    def decode_attention_static(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor, layer0=0, flags=0):
+        """decode_attention with the split partials in the library's static device array; `out`
+        must be supplied (this call allocates nothing)."""
+        assert q.is_contiguous() and q.dtype == torch.float16 and q.dim() == 4
+        assert out.is_contiguous() and out.dtype == torch.float32 and out.shape == q.shape
+        _check(lib().xq_decode_attention_static(self._h, layer0, q.shape[0], C.c_void_p(q.data_ptr()),
+                                                C.c_void_p(out.data_ptr()), float(sm_scale), int(flags), _stream()),
+               "xq_decode_attention_static")
         return out
 
     def unpack_codes(self, layer, is_v):

@@ -5,11 +5,37 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "xq_internal.h"
 
+// Split partials of xq_decode_attention_static: one array per GPU, held from the load of the
+// library's code on that GPU until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returned.
+static __device__ __align__(256) unsigned char scratch[XQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];  // address of `scratch` on each device, once resolved there
+
+// Address of the current device's copy of `scratch` (resolved once per device, with that device
+// current).  The first resolution on a device may load the library's code there, so it is done
+// from xq_cache_create as well, outside any stream capture.
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return XQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return XQ_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return XQ_OK;
+}
 
 inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 
@@ -285,6 +311,8 @@ int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, x
         delete c;
         return XQ_ERR_HIP;
     }
+    void *unused = nullptr;
+    (void)static_scratch(&unused);  // resolve this device's scratch array now; a failure is reported by the call that needs it
     *out = c;
     return XQ_OK;
 }
@@ -601,9 +629,10 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
     return XQ_OK;
 }
 
-int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
-                        void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
-                        int32_t flags, void *hip_stream) {
+// Plans and enqueues the decode launches of a call; the split partials go to dev_workspace.
+static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
+                       void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
+                       int32_t flags, void *hip_stream) {
     if (!range_ok(cache, layer0, n_layers) || !q_f16 || !out_f32 || !dev_workspace) return XQ_ERR_INVALID_ARG;
     if (flags & ~(XQ_DECODE_PAIR_FUSED | XQ_DECODE_VECTOR_ALU)) return XQ_ERR_INVALID_ARG;
     if (((uintptr_t)q_f16 & 3) || ((uintptr_t)out_f32 & 3) || ((uintptr_t)dev_workspace & 15)) return XQ_ERR_INVALID_ARG;
@@ -723,6 +752,24 @@ int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers,
         if (xq_launch_merge(a, c.head_dim, e - l, s) != hipSuccess) return XQ_ERR_HIP;
     }
     return XQ_OK;
+}
+
+int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
+                        void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
+                        int32_t flags, void *hip_stream) {
+    return decode_impl(cache, layer0, n_layers, q_f16, out_f32, sm_scale, dev_workspace, workspace_bytes, flags,
+                       hip_stream);
+}
+
+int xq_decode_attention_static(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
+                               void *out_f32, float sm_scale, int32_t flags, void *hip_stream) {
+    if (!cache) return XQ_ERR_INVALID_ARG;
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+    // decode_impl answers XQ_ERR_CAPACITY when the call's partials exceed XQ_STATIC_SCRATCH_BYTES
+    return decode_impl(cache, layer0, n_layers, q_f16, out_f32, sm_scale, ws, XQ_STATIC_SCRATCH_BYTES, flags,
+                       hip_stream);
 }
 
 int xq_unpack_codes(const xq_cache *cache, int32_t layer, int32_t is_v, uint8_t *dev_codes_u8, void *hip_stream) {
