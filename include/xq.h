@@ -181,7 +181,11 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * workgroup serve both layers of a pair that shares key and value codes, so that the common
  * codes are fetched and unpacked once (the result is the same up to fp32 summation order; pairs
  * that share only one of the two, or not at all, run one layer per workgroup as without it).  All layers in the range must hold
- * the same, non-zero number of tokens per sequence (sequences may differ from one another). */
+ * the same, non-zero number of tokens per sequence (sequences may differ from one another), and a
+ * layer outside the range whose codes a layer of the range reads must hold at least as many packed
+ * tokens (XQ_ERR_STATE otherwise: e.g. the second layer of a pair decoded before the first was
+ * packed, or, with share_dominant > 0, a layer decoded at a ring-flush step before the group's
+ * storing layer was appended). */
 #define XQ_DECODE_PAIR_FUSED 1
 /* With head_dim 128 the multiply-adds run on the 4x4x4 fp16 matrix instruction (rows = query
  * heads of the kv head and layers of the pair, times the two fp16 halves of a key weight);

@@ -643,8 +643,19 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
         if (row[i] < 1) return XQ_ERR_STATE;
         if (row[i] > T) T = row[i];
     }
-    for (int l = layer0; l < layer0 + n_layers; ++l)
+    for (int l = layer0; l < layer0 + n_layers; ++l) {
         if (!rows_equal(cache, l, layer0)) return XQ_ERR_STATE;
+        // the layer whose codes l reads may lie outside the range: it must already hold every
+        // packed group that l's metadata describes
+        for (int v = 0; v < 2; ++v) {
+            const int cl = code_layer(c, l, v != 0);
+            if (cl == l) continue;
+            for (int i = 0; i < c.batch; ++i)
+                if (xq_quantized_len(len_row(cache, cl)[i], c.group, c.residual) <
+                    xq_quantized_len(row[i], c.group, c.residual))
+                    return XQ_ERR_STATE;
+        }
+    }
     const bool ragged = !row_uniform(cache, layer0);
     if (ragged && c.batch > XQ_MAX_RAGGED) return XQ_ERR_UNSUPPORTED;
     const int Tq = xq_quantized_len(T, c.group, c.residual);

@@ -464,6 +464,55 @@ def test_determinism_and_error_codes(lib_):
     c2.close()
 
 
+def test_decode_refuses_code_layer_that_lags(lib_):
+    """A layer that reads another layer's codes cannot be decoded before that layer holds them:
+    the odd layer of a pair whose first layer is still empty, and, with the storing layer above
+    its reader (share_dominant = 1), a ring-flush step at which only the reader was appended."""
+    tl = lib_
+    from paper_2510_11236_amd import XqError
+    base = synth.scaled(synth.workloads()[1], n_layers=2, batch=1, n_q_heads=2, n_kv_heads=2, km=0, vm=0,
+                        eta1=1 / 6, eta2=0.045, seed=61)
+    sigma = 1.0 / np.sqrt(128)
+    # (a) pair (0, 1), only layer 1 packed
+    T = 500
+    K, V = synth.kv_all(base, T)
+    Kd, Vd = K.cuda(), V.cuda()
+    q = synth.queries(base).cuda()
+    cache = tl.make_cache(base, max_tokens=T)
+    cache.quantize_pack(Kd[1:], Vd[1:], layer0=1)
+    with pytest.raises(XqError) as e:
+        cache.decode_attention(q[1:], sigma, layer0=1)
+    assert e.value.code == -4
+    cache.quantize_pack(Kd[:1], Vd[:1], layer0=0)
+    out = torch.zeros(q.shape, dtype=torch.float32, device="cuda")
+    cache.decode_attention(q[1:], sigma, out=out[1:], layer0=1)
+    cache.decode_attention(q[:1], sigma, out=out[:1], layer0=0)
+    for h in range(2):
+        st = tl.oracle_slice(base, K, V, 0, h)
+        tl.check_attention(out, base, tl.oracle_attention(base, st, q, 0, h, sigma), 0, h)
+    cache.close()
+    # (b) layer 0 reads layer 1's codes; prefill leaves the ring full, so the next append flushes
+    w = synth.scaled(base, share_dominant=1, seed=62)
+    T0 = 128 + 3 * 32
+    K, V = synth.kv_all(w, T0 + 1)
+    Kd, Vd = K.cuda(), V.cuda()
+    cache = tl.make_cache(w, max_tokens=T0 + 1)
+    cache.quantize_pack(Kd[:, :, :, :T0], Vd[:, :, :, :T0])
+    assert cache.length(0) == (T0, T0 - 128)
+    cache.append_token(Kd[:1, :, :, T0].contiguous(), Vd[:1, :, :, T0].contiguous(), layer0=0)
+    assert cache.length(0) == (T0 + 1, T0 - 128 + 32) and cache.length(1) == (T0, T0 - 128)
+    with pytest.raises(XqError) as e:
+        cache.decode_attention(q[:1], sigma, layer0=0)
+    assert e.value.code == -4
+    cache.append_token(Kd[1:, :, :, T0].contiguous(), Vd[1:, :, :, T0].contiguous(), layer0=1)
+    out = cache.decode_attention(q, sigma)
+    for h in range(2):
+        st = tl.oracle_slice(w, K, V, 0, h)
+        tl.check_stored(cache, w, st, 0, h)
+        tl.check_attention(out, w, tl.oracle_attention(w, st, q, 0, h, sigma), 0, h)
+    cache.close()
+
+
 def test_code_delta_histogram(lib_):
     """Sec. 3.3.2 diagnostic: adjacent-layer code differences counted on the device equal the
     counts from the oracle's codes; on the correlated synthetic layers most differences are 0/1."""
