@@ -106,6 +106,8 @@ def main():
                     help="keep the packed tokens in pool pages of this many tokens (0: one region per sequence)")
     ap.add_argument("--vector-alu", action="store_true",
                     help="decode with the vector-ALU kernels instead of the matrix-instruction ones")
+    ap.add_argument("--matrix-f16", action="store_true",
+                    help="matrix-instruction kernels with 2-bit keys kept on the 4x4x4 fp16 instruction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-slices", type=int, default=96)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -219,7 +221,7 @@ def main():
 
     # --schedule auto times both schedules (untimed probes) and takes the faster; an explicit
     # schedule runs no probes, so that a profile of the run holds only warmup + timed launches
-    alu = 2 if args.vector_alu else 0
+    alu = 2 if args.vector_alu else (4 if args.matrix_f16 else 0)
     can_fuse = any(l % 2 == 1 and (l >= w.km or l >= w.vm) for l in range(w.n_layers))
     probe = {}
     if args.schedule == "auto":

@@ -192,6 +192,11 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * XQ_DECODE_VECTOR_ALU selects the kernels that do them on the vector ALU instead (always
  * used for head_dim 64).  Both meet the same error bound. */
 #define XQ_DECODE_VECTOR_ALU 2
+/* Matrix family only: 2-bit key codes are by default multiplied on the 16x16x128 fp8 x fp4 matrix
+ * instruction (a 2-bit code in a nibble is the fp4 number code / 2, so one AND isolates eight codes;
+ * the key weights travel as four fp8 terms, 16 significant bits).  XQ_DECODE_MATRIX_F16 keeps the
+ * keys on the 4x4x4 fp16 instruction like the values (1-bit keys always are).  Same error bound. */
+#define XQ_DECODE_MATRIX_F16 4
 int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
                         void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                         int32_t flags, void *hip_stream);

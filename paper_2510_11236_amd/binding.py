@@ -16,6 +16,7 @@ _LIB = None
 
 XQ_DECODE_PAIR_FUSED = 1
 XQ_DECODE_VECTOR_ALU = 2
+XQ_DECODE_MATRIX_F16 = 4
 
 
 class XqError(RuntimeError):

@@ -31,6 +31,10 @@ def _jobs():
                 for bv in (1, 2):
                     jobs.append((f"xq_decode_{D}_{G}_{bk}{bv}.o", "xq_decode.hip",
                                  [f"-DXQ_D={D}", f"-DXQ_G={G}", f"-DXQ_BK={bk}", f"-DXQ_BV={bv}"]))
+    for G in (32, 64):      # the kernels with the fp8 x fp4 key phase: head_dim 128, 2-bit keys
+        for bv in (1, 2):
+            jobs.append((f"xq_decode_kx_128_{G}_2{bv}.o", "xq_decode.hip",
+                         ["-DXQ_KX_TU", "-DXQ_D=128", f"-DXQ_G={G}", "-DXQ_BK=2", f"-DXQ_BV={bv}"]))
     return jobs
 
 

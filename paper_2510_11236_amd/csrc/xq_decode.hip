@@ -18,6 +18,8 @@
 //   value phase  lane = D/64 channels x all 128 tokens; the weights p*s^ come from LDS
 // Every "virtual head" v = (layer in pair) * NREP + (query head in GQA group) has its own
 // weights and accumulators and shares the unpacked codes.
+#include <type_traits>
+
 #include "xq_internal.h"
 
 #if !defined(XQ_D) || !defined(XQ_G) || !defined(XQ_BK) || !defined(XQ_BV)
@@ -30,6 +32,9 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+typedef int int8_v __attribute__((ext_vector_type(8)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float hbits(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
 
@@ -78,6 +83,27 @@ __device__ __forceinline__ half4_t codes4(uint32_t lo, uint32_t hi) {
     uint2_t u = {lo, hi};
     return __builtin_bit_cast(half4_t, u);
 }
+// KX key path: v_mfma_f32_16x16x128_f8f6f4 with the weights as A (fp8 e4m3, rows) and the codes
+// as B (fp4 e2m1, columns = 16 tokens).  A 2-bit code in the low bits of a nibble IS the fp4
+// number c/2 (patterns 0000, 0001, 0010, 0011 = 0, 0.5, 1, 1.5), so one AND isolates eight codes.
+// Operand layout of the instruction (found by one-hot probes on the device): lane l supplies row
+// (A) / column (B) l % 16; with q = l / 16, B's nibble e holds k = 32 q + e, and A's byte e holds
+// k = 16 q + e (e < 16) or 64 + 16 q + e - 16 (e >= 16); C: lane l, register x = row 4 (l / 16) + x
+// of column l % 16.
+__device__ __forceinline__ float4_t mfma_fp8_fp4(int8_v a, int8_v b, float4_t c) {
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0 /* A: fp8 e4m3 */, 4 /* B: fp4 */, 0, 0, 0, 0);
+}
+// fp8(x / scale), fp8(y / scale) into the low or high half of a dword (scale a power of two; no
+// saturation: |x / scale| must stay below 464), and back: fp8 * scale.
+template <bool HI>
+__device__ __forceinline__ uint32_t cvt_fp8x2(uint32_t old, float x, float y, float scale) {
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(__builtin_bit_cast(short2_t, old), x, y, scale, HI));
+}
+template <bool HI>
+__device__ __forceinline__ float2_t fp8x2_back(uint32_t v, float scale) {
+    return __builtin_amdgcn_cvt_scalef32_pk_f32_fp8((int)v, scale, HI);
+}
+
 template <int W>
 __device__ __forceinline__ uint32_t group_umax(uint32_t v) {  // max over aligned groups of W lanes
 #pragma unroll
@@ -151,10 +177,12 @@ __device__ __forceinline__ float exp2_le0(float x) { return __builtin_amdgcn_exp
 // (Held to 128 registers, 4 waves per SIMD, where that costs no spill: the one- and two-head matrix
 // kernels and the four-head one at g = 64 unless keys and values are both 2-bit; +2 to 5 %.  The
 // others spill when squeezed and keep their 3 or 2 waves.)
-template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false, bool MM = false>
+template <int D, int G, int BK, int BV, int NREP, int NLAY, bool REUSE = false, bool MM = false, bool KX = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(
-    MM && (NREP * NLAY <= 2 || (NREP == 4 && NLAY == 1 && G == 64 && BK + BV < 4)) ? 4 : 1, 8)))
+    MM && !KX && (NREP * NLAY <= 2 || (NREP == 4 && NLAY == 1 && G == 64 && BK + BV < 4)) ? 4 : 1, 8)))
 void xq_decode_kernel(XqDecodeArgs a) {
+    static_assert(!KX || (MM && BK == 2 && D == 128 && NREP * NLAY >= 4),
+                  "the fp8 x fp4 key path: matrix family, 2-bit keys, head_dim 128, at least four virtual heads");
     constexpr int NV = NREP * NLAY;       // virtual heads
     constexpr int CPL = D / 64;           // value channels per lane
     constexpr int NJ = D / G;             // value groups per token
@@ -189,12 +217,16 @@ void xq_decode_kernel(XqDecodeArgs a) {
     // (rows padded so that the 4 rows of a wave, which read different groups, hit different banks)
     typedef float KwT[NV][NGT][D + 4];
     typedef _Float16 KaT[NKS][NGT][32][4][4];  // matrix path: [row set][group][A matrix][row][k]
+    // fp8 x fp4 key path: [group][row = 4 * virtual head + term][128 bytes in the instruction's A order],
+    // rows padded to 144 bytes so that the 16 rows a quarter wave reads start in different banks
+    constexpr int KXROW = 36;
+    typedef uint32_t KxT[NGT][4 * NV][KXROW];
     // (value-weight rows: padded by 8 halves against bank conflicts of the vector path's 16-byte
     // reads; the matrix path reads 8 bytes per lane from a few broadcast addresses and goes without,
     // which is what lets three workgroups of the four-head g = 32 kernel share a CU's LDS)
     typedef _Float16 VwT[NV][4][NJ][32 + (MM ? 0 : 8)];
     typedef float PartT[NV][D + 2];
-    constexpr int KW_BYTES = 4 * (int)(MM ? sizeof(KaT) : sizeof(KwT)), PART_BYTES = 4 * (int)sizeof(PartT);
+    constexpr int KW_BYTES = 4 * (int)(KX ? sizeof(KxT) : MM ? sizeof(KaT) : sizeof(KwT)), PART_BYTES = 4 * (int)sizeof(PartT);
     constexpr int KP_BYTES = KW_BYTES > PART_BYTES ? KW_BYTES : PART_BYTES;
     // with several heads the scaled queries live in LDS rather than in 8 registers per head
     constexpr bool Q_LDS = NV >= 2 || MM;
@@ -202,6 +234,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
     __shared__ __attribute__((aligned(16))) char s_raw[KP_BYTES + 4 * sizeof(VwT) + (Q_LDS ? sizeof(QT) : 0)];
     KwT *s_kw = (KwT *)s_raw;
     KaT *s_ka = (KaT *)s_raw;
+    KxT *s_kx = (KxT *)s_raw;
     VwT *s_vw = (VwT *)(s_raw + KP_BYTES);
     PartT *s_part = (PartT *)s_raw;
     QT &s_q = *(QT *)(s_raw + KP_BYTES + 4 * sizeof(VwT));
@@ -286,13 +319,19 @@ void xq_decode_kernel(XqDecodeArgs a) {
         float kpw[MM ? NPL : 1][2];
         int eq[MM ? NV : 1];
         float qsc[MM ? NV : 1];
+        // fp8 x fp4 key path, preparation role: an 8-channel span of the lane's group; when a group has
+        // 32 lanes, the two lanes of a span split the query heads of each layer between them
+        constexpr int HP = LPG / 16;                       // lanes per span
+        constexpr int NPH = NREP >= HP ? NREP / HP : 1;    // query heads of a layer that one lane prepares
+        constexpr int QE = KX ? 8 : 14;                    // the query table holds q 2^(QE - e): weights below 2^QE
+        const int span = li % 16, hp = li / 16;
         if constexpr (MM) {
 #pragma unroll
             for (int x = 0; x < NVS; ++x)
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) accm[x][c] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < NPL; ++e) {
+            for (int e = 0; e < (KX ? 0 : NPL); ++e) {
                 const int n = li * NPL + e, ci = n / 2, p0 = 2 * (n % 2), p4 = (ci % CPB) * 4;
                 kch[e] = (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + p4 + p0;
                 kpw[e][0] = __builtin_ldexpf(1.0f, -BK * (p4 + p0));
@@ -311,7 +350,8 @@ void xq_decode_kernel(XqDecodeArgs a) {
             for (int idx = tid; idx < NV * D; idx += 256) {
                 const int v = idx / D, pos = idx % D, n = pos / 4, k = pos % 4;
                 const int ci = n / 2, p = 2 * (n % 2) + k / 2;
-                const int ch = (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4 + p + (k % 2) * HALFK;
+                const int ch = KX ? pos  // (the fp8 x fp4 path reads its channels in natural order)
+                                  : (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4 + p + (k % 2) * HALFK;
                 s_q[v][pos] = hbits(qptr(v)[ch]) * a.scale_log2e;
             }
             __syncthreads();
@@ -321,7 +361,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 int e = (int)((__float_as_uint(mx) >> 23) & 0xffu) - 126;  // 2^e > |q| of every channel
                 e = __builtin_amdgcn_readfirstlane(min(max(e, -40), 60));
                 eq[v] = e;
-                qsc[v] = __uint_as_float((uint32_t)(127 - 14 + e) << 23);  // 2^(e - 14)
+                qsc[v] = __uint_as_float((uint32_t)(127 - QE + e) << 23);  // 2^(e - QE)
             }
             // the table keeps q 2^(14 - e): weights come out in fp16 range without a multiply per
             // channel, and the zero-point sum is scaled back once per head
@@ -330,7 +370,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 const int v = idx / D;
                 float f = 1.0f;
 #pragma unroll
-                for (int u = 0; u < NV; ++u) f = (u == v) ? __uint_as_float((uint32_t)(127 + 14 - eq[u]) << 23) : f;
+                for (int u = 0; u < NV; ++u) f = (u == v) ? __uint_as_float((uint32_t)(127 + QE - eq[u]) << 23) : f;
                 s_q[v][idx % D] *= f;
             }
             __syncthreads();
@@ -362,10 +402,12 @@ void xq_decode_kernel(XqDecodeArgs a) {
         // The plain path loads them inside the tile's own iteration.  The matrix path spends less
         // time per tile and keeps a tile's worth of loads in flight instead: each set is reloaded
         // for the wave's next tile as soon as the current tile has consumed it.
-        uint32_t kc[2][WK];
+        // (fp8 x fp4 key path: kc[m] = the two words of token 16 m + lane % 16 that hold channels
+        // 32 (lane / 16) .. + 31; kmeta = scale | zero of the 8 channels of the lane's span)
+        uint32_t kc[KX ? 8 : 2][KX ? 2 : WK];
         uint32_t vc[4][WS];
         uint32_t vm[NLAY][2][NJ];
-        uint32_t kmeta[MM ? NLAY : 1][MM ? NPL : 1][4];
+        uint32_t kmeta[MM ? NLAY : 1][KX ? 2 : (MM ? NPL : 1)][4];
         struct TileAt {
             int tile, tin;   // tile number; index of its first token inside the slice
             int64_t slice;   // where its 128 tokens are stored: the sequence's own slice, or a page's
@@ -377,7 +419,16 @@ void xq_decode_kernel(XqDecodeArgs a) {
             return t;
         };
         auto load_kmeta = [&](const TileAt &t) {
-            if constexpr (MM) {
+            if constexpr (KX) {
+                // (a key group past the sequence's last one reads the tile's last valid group -- see load_kcodes)
+                const int gic = min(gi, (min(seqTq - t.tile * XQ_TILE_TOKENS, XQ_TILE_TOKENS) + G - 1) / G - 1);
+#pragma unroll
+                for (int y = 0; y < NLAY; ++y) {
+                    const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].k_meta + t.slice * a.st.k_meta) +
+                                         (int64_t)(t.tin / G + gic) * D + 8 * span;
+                    VecLoad<8>::ld(mp, &kmeta[y][0][0]);
+                }
+            } else if constexpr (MM) {
                 const bool g_ok = (t.tile * NGT + gi) * G < seqTq;
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y)
@@ -397,32 +448,53 @@ void xq_decode_kernel(XqDecodeArgs a) {
                     }
             }
         };
+        // In the kernels with the fp8 x fp4 key phase, blocks of a tile past the sequence's last one are
+        // read from the tile's last valid block instead of being skipped: their scores are masked and
+        // their softmax weights are zero, and a load that is always issued keeps the count of loads in
+        // flight the same on every path, which is what lets the waits in the loop name a count (a load
+        // that may be skipped forces the next wait to be a wait for all).  The other kernels skip and zero.
         auto load_kcodes = [&](const TileAt &t) {
-            const bool row_ok = t.tile * 4 + row < n_blocks;
-            const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
-                                                    t.slice * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
-                                 (int64_t)(t.tin / 32 + row) * 32 * WK;
+            if constexpr (KX) {
+                // column block m of the tile = tokens 16 m .. 16 m + 15; this lane: token r16 of it,
+                // row words 2 (lane / 16), + 1 = half of 16-byte chunk (lane / 32) of the row
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes + t.slice * a.st.k_codes2) +
+                                     (int64_t)(t.tin / 32) * 32 * WK + (row / 2) * 32 * CWK + r16 * CWK + 2 * (row % 2);
+                const int last = min(n_blocks - t.tile * 4, 4) - 1;  // >= 0: the tile holds at least one block
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+                for (int m = 0; m < 8; ++m) VecLoad<2, !REUSE>::ld(cp + min(m / 2, last) * 32 * WK + (m % 2) * 16 * CWK, kc[m]);
+            } else {
+                const bool row_ok = t.tile * 4 + row < n_blocks;
+                const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].k_codes +
+                                                        t.slice * (BK == 2 ? a.st.k_codes2 : a.st.k_codes1)) +
+                                     (int64_t)(t.tin / 32 + row) * 32 * WK;
 #pragma unroll
-                for (int ch = 0; ch < NCH; ++ch) {
-                    if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
-                    else {
+                for (int s = 0; s < 2; ++s)
 #pragma unroll
-                        for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        if (row_ok) VecLoad<CWK, !REUSE>::ld(cp + ch * 32 * CWK + (r16 + 16 * s) * CWK, &kc[s][ch * CWK]);
+                        else {
+#pragma unroll
+                            for (int w = 0; w < CWK; ++w) kc[s][ch * CWK + w] = 0;
+                        }
                     }
-                }
+            }
         };
         auto load_values = [&](const TileAt &t) {
-            const bool row_ok = t.tile * 4 + row < n_blocks;
+            const int last = min(n_blocks - t.tile * 4, 4) - 1;
+            const bool row_ok = KX || row <= last;
+            const int rowc = KX ? min(row, last) : row;
             const uint32_t *cp = (const uint32_t *)(a.arena + dsc[0].v_codes +
                                                     t.slice * (BV == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) {
-                if (t.tile * 4 + kb < n_blocks) VecLoad<WS, !REUSE>::ld(cp + (int64_t)(t.tin / 32 + kb) * 64 * WS + lane * WS, vc[kb]);
-                else {
+                if constexpr (KX) {
+                    VecLoad<WS, !REUSE>::ld(cp + (int64_t)(t.tin / 32 + min(kb, last)) * 64 * WS + lane * WS, vc[kb]);
+                } else {
+                    if (kb <= last) VecLoad<WS, !REUSE>::ld(cp + (int64_t)(t.tin / 32 + kb) * 64 * WS + lane * WS, vc[kb]);
+                    else {
 #pragma unroll
-                    for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
+                        for (int w = 0; w < WS; ++w) vc[kb][w] = 0;
+                    }
                 }
             }
 #pragma unroll
@@ -430,7 +502,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     const uint32_t *mp = (const uint32_t *)(a.arena + dsc[y].v_meta + t.slice * a.st.v_meta) +
-                                         ((int64_t)(t.tin / 32 + row) * 32 + r16 + 16 * s) * NJ;
+                                         ((int64_t)(t.tin / 32 + rowc) * 32 + r16 + 16 * s) * NJ;
                     if (row_ok) VecLoad<NJ>::ld(mp, vm[y][s]);
                     else {
 #pragma unroll
@@ -450,10 +522,20 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 load_values(t);
             }
         }
+        // One tile of the wave.  more: the wave has a further tile, whose register sets are reloaded
+        // inside this one.  The translation units that build the kernels with the fp8 x fp4 key phase
+        // (XQ_KX_TU) make that a compile-time flag and run the wave's last tile in a second copy of the
+        // body without those loads, so that in the steady-state copy every load is issued on every path
+        // (see load_kcodes); the other kernels keep the plain loop.
+#ifdef XQ_KX_TU
+        auto one_tile = [&](auto more_flag) __attribute__((always_inline)) {
+            constexpr bool more = decltype(more_flag)::value;
+#else
         for (int it = wave; it < n_tiles; it += 4) {
+            const bool more = it + 4 < n_tiles;
+#endif
             const TileAt cur = tile_at(pos);
-            const bool more = it + 4 < n_tiles;  // then n_tiles > 4 and one subtraction wraps pos + 4
-            pos = pos + 4 >= n_tiles ? pos + 4 - n_tiles : pos + 4;
+            pos = pos + 4 >= n_tiles ? pos + 4 - n_tiles : pos + 4;  // (a further tile means n_tiles > 4: one subtraction wraps)
             const TileAt nxt = (MM && more) ? tile_at(pos) : cur;
             const int tile = cur.tile, tin = cur.tin;
             const int64_t slice = cur.slice;
@@ -461,7 +543,77 @@ void xq_decode_kernel(XqDecodeArgs a) {
             // ---- key weights for the tile's groups -> LDS
             float zs[NV];
             float fac[MM ? NV : 1];  // matrix path: score = (sum of the head's two rows) * fac + zs
-            if constexpr (MM) {
+            if constexpr (KX) {
+                if constexpr (!PIPE_KMETA) load_kmeta(cur);
+                // where this lane's span goes in a row of the A table: 16-channel span s16 sits in the
+                // quarter s16 % 4 of the row's lanes, first or second 16 bytes by s16 / 4; its even
+                // channels fill two dwords (by half of the span), its odd channels the two after them
+                const int off_e = (span / 2 % 4) * 8 + (span / 8) * 4 + span % 2;  // dword of the even channels; odd: + 2
+#pragma unroll
+                for (int y = 0; y < NLAY; ++y) {
+                    uint32_t hm = 0;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) hm = max(hm, kmeta[y][k / 4][k % 4] & 0x7fffu);
+                    hm = group_umax<LPG>(hm);
+                    const int es = max((int)(hm >> 10), 1) - 14;  // 2^es > every scale of the group
+#pragma unroll
+                    for (int x = 0; x < NPH; ++x) {
+                        const int n = NREP >= HP ? hp + HP * x : 0, v = y * NREP + n;  // (runtime when HP = 2)
+                        const float4 qa = *(const float4 *)&s_q[v][8 * span], qb = *(const float4 *)&s_q[v][8 * span + 4];
+                        const float qv[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+                        float w[8], zp = 0.f;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const uint32_t mt = kmeta[y][k / 4][k % 4];
+                            w[k] = qv[k] * hbits(mt & 0xffffu);  // q 2^(QE - eq) * scale: |w| < 2^(QE + es)
+                            zp = fmaf(qv[k], hbits(mt >> 16), zp);
+                        }
+                        // w 2^-es = t0 + t1 / 16 + t2 / 256 + t3 / 4096 (+ at most 2^-16 |w|), every t an fp8
+                        // number below 2^8: four rows of A.  The conversions divide by their scale operand,
+                        // the residuals are exact in fp32.
+                        uint32_t *dst = &s_kx[wave][gi][4 * v][off_e];
+                        uint32_t ev = 0, od = 0;  // (both halves are overwritten below)
+#pragma unroll
+                        for (int tau = 0; tau < 4; ++tau) {
+                            const float sc = __uint_as_float((uint32_t)(127 + es - 4 * tau) << 23);  // 2^es 16^-tau
+                            ev = cvt_fp8x2<false>(ev, w[0], w[2], sc);
+                            od = cvt_fp8x2<false>(od, w[1], w[3], sc);
+                            ev = cvt_fp8x2<true>(ev, w[4], w[6], sc);
+                            od = cvt_fp8x2<true>(od, w[5], w[7], sc);
+                            if (NREP >= HP || hp == 0) {
+                                dst[tau * KXROW] = ev;
+                                dst[tau * KXROW + 2] = od;
+                            }
+                            if (tau < 3) {
+                                const float2_t e0 = fp8x2_back<false>(ev, sc), e1 = fp8x2_back<true>(ev, sc);
+                                const float2_t o0 = fp8x2_back<false>(od, sc), o1 = fp8x2_back<true>(od, sc);
+                                w[0] -= e0[0]; w[2] -= e0[1]; w[4] -= e1[0]; w[6] -= e1[1];
+                                w[1] -= o0[0]; w[3] -= o0[1]; w[5] -= o1[0]; w[7] -= o1[1];
+                            }
+                        }
+                        // zero-point sum of the head over the 16 spans; the heads the other lane of the
+                        // span prepared come from it
+                        float qs = qsc[0];
+#pragma unroll
+                        for (int u = 1; u < NV; ++u) qs = (u == v) ? qsc[u] : qs;
+                        const float zmine = group_sum<16>(zp) * qs;
+                        if constexpr (HP == 2 && NREP >= 2) {
+                            const float zother = __shfl_xor(zmine, 16, 64);
+                            zs[y * NREP + 2 * x] = hp == 0 ? zmine : zother;
+                            zs[y * NREP + 2 * x + 1] = hp == 0 ? zother : zmine;
+                        } else {
+                            zs[y * NREP + x] = zmine;
+                        }
+                    }
+                    // the instruction sums (weight 2^(QE - es - eq)) (code / 2): score = sum * 2^(es + eq - QE + 1)
+#pragma unroll
+                    for (int n = 0; n < NREP; ++n)
+                        fac[y * NREP + n] = __uint_as_float((uint32_t)(127 + 1 - QE + es + eq[y * NREP + n]) << 23);
+                }
+                if constexpr (PIPE_KMETA) {
+                    if (more) load_kmeta(nxt);
+                }
+            } else if constexpr (MM) {
                 if constexpr (!PIPE_KMETA) load_kmeta(cur);
 #pragma unroll
                 for (int y = 0; y < NLAY; ++y) {
@@ -568,7 +720,68 @@ void xq_decode_kernel(XqDecodeArgs a) {
             // ---- q . K^ over the packed codes
             float tsum[2][NV];  // code part of the scores of this lane's two tokens
             const int kg = (row * 32) / G;  // key group of this row inside the tile
-            if constexpr (MM) {
+            if constexpr (KX) {
+                // One instruction per 16 tokens (column block m) and 4 virtual heads: rows 4 h .. 4 h + 3
+                // are the four fp8 terms of head h, so lane (token r16, quarter row) receives the four
+                // partial scores of head `row` and folds them.  A changes with the key group.
+                constexpr int NSET = (NV + 3) / 4, MPG = G / 16;  // row sets; column blocks per key group
+                float xs[NSET][8];
+                float4_t pc = {0.f, 0.f, 0.f, 0.f};
+                int px = 0, pm = 0;
+#pragma unroll
+                for (int gq = 0; gq < NGT; ++gq) {
+                    int8_v ka[NSET];
+#pragma unroll
+                    for (int x = 0; x < NSET; ++x) {
+                        const int rr = min(16 * x + r16, 4 * NV - 1);  // rows past the last head repeat it; nobody reads them
+                        const uint4 lo = *(const uint4 *)&s_kx[wave][gq][rr][row * 8], hi = *(const uint4 *)&s_kx[wave][gq][rr][row * 8 + 4];
+                        ka[x] = int8_v{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+                    }
+#pragma unroll
+                    for (int mm = 0; mm < MPG; ++mm) {
+                        const int m = gq * MPG + mm;
+                        constexpr uint32_t NIB = 0x33333333u;
+                        const int8_v kb = {(int)(kc[m][0] & NIB), (int)((kc[m][0] >> 2) & NIB), (int)(kc[m][1] & NIB),
+                                           (int)((kc[m][1] >> 2) & NIB), 0, 0, 0, 0};
+#pragma unroll
+                        for (int x = 0; x < NSET; ++x) {
+                            // (the result is folded one step later, behind the next instruction's issue)
+                            const float4_t c = mfma_fp8_fp4(ka[x], kb, float4_t{0.f, 0.f, 0.f, 0.f});
+                            if (m > 0 || x > 0) xs[px][pm] = fmaf(fmaf(fmaf(pc[3], 0.0625f, pc[2]), 0.0625f, pc[1]), 0.0625f, pc[0]);
+                            pc = c;
+                            px = x;
+                            pm = m;
+                        }
+                    }
+                }
+                xs[px][pm] = fmaf(fmaf(fmaf(pc[3], 0.0625f, pc[2]), 0.0625f, pc[1]), 0.0625f, pc[0]);
+                // xs[x][m] = score of (token 16 m + r16, head 4 x + row); wanted: lane (r16, row) holds tokens
+                // 32 row + 16 s + r16 for every head.  A 4 x 4 transpose over the lanes 16 apart in two
+                // rounds of swaps: column blocks 4..7 go to the upper half wave, then 2..3 (6..7) to the odd rows.
+#pragma unroll
+                for (int x = 0; x < NSET; ++x) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(xs[x][m]), __float_as_uint(xs[x][m + 4]), false, false);
+                        xs[x][m] = __uint_as_float(r[0]);      // heads 0, 1 (by row % 2) of blocks 0..3 | 4..7
+                        xs[x][m + 4] = __uint_as_float(r[1]);  // heads 2, 3
+                    }
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            if (4 * x + 2 * hh >= NV) continue;
+                            const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(xs[x][4 * hh + s2]),
+                                                                            __float_as_uint(xs[x][4 * hh + s2 + 2]), false, false);
+                            xs[x][4 * hh + s2] = __uint_as_float(r[0]);      // head 2 hh
+                            xs[x][4 * hh + s2 + 2] = __uint_as_float(r[1]);  // head 2 hh + 1
+                        }
+                }
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) tsum[s2][v] = xs[v / 4][4 * ((v % 4) / 2) + 2 * (v % 2) + s2] * fac[v];
+            } else if constexpr (MM) {
                 // the lanes of a token group are the lanes that prepared it (kg == gi); A matrix n
                 // sits in block n % NB of register pair n / NB
                 constexpr int NCHUNK = WK * 2 * CPB;
@@ -814,7 +1027,16 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 }
             }
             wave_lds_fence();
+#ifdef XQ_KX_TU
+        };
+        {
+            int it = wave;
+            for (; it + 4 < n_tiles; it += 4) one_tile(std::true_type{});
+            if (it < n_tiles) one_tile(std::false_type{});
         }
+#else
+        }
+#endif
         // ---- wave totals
         const int jl = (lane * CPL) / G;
 #pragma unroll
@@ -954,6 +1176,22 @@ hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipSt
     XqDecodeArgs b = a;
     b.n_launch_z = pair_fused ? n_layers / 2 : n_layers;
     dim3 grid((unsigned)((a.n_splits + 1) * a.batch * a.n_kv_heads * b.n_launch_z));
+#ifdef XQ_KX_TU
+    // the kernels with the fp8 x fp4 key phase: at least four (query head, layer) pairs per kv head
+    if constexpr (D == 128 && BK == 2 && NREP >= 2) {
+        if (pair_fused) {
+            if constexpr (2 * NREP * (XQ_TILE_TOKENS / G) <= 16) {
+                xq_decode_kernel<D, G, BK, BV, NREP, 2, false, true, true><<<grid, block, 0, s>>>(b);
+                return hipGetLastError();
+            }
+        } else if constexpr (NREP >= 4) {
+            if (a.reuse_codes) xq_decode_kernel<D, G, BK, BV, NREP, 1, true, true, true><<<grid, block, 0, s>>>(b);
+            else xq_decode_kernel<D, G, BK, BV, NREP, 1, false, true, true><<<grid, block, 0, s>>>(b);
+            return hipGetLastError();
+        }
+    }
+    return hipErrorInvalidValue;
+#else
     constexpr bool HAS_MM = D == 128;  // the matrix path is built for head_dim 128
     if (a.matrix && !HAS_MM) return hipErrorInvalidValue;
     if (pair_fused) {
@@ -978,11 +1216,16 @@ hipError_t launch_cfg(const XqDecodeArgs &a, int n_layers, int pair_fused, hipSt
         else xq_decode_kernel<D, G, BK, BV, NREP, 1><<<grid, block, 0, s>>>(b);
     }
     return hipGetLastError();
+#endif
 }
 
 }  // namespace
 
+#ifdef XQ_KX_TU
+#define XQ_CAT2(a, b, c, d) xq_launch_decode_kx_##a##_##b##_##c##d
+#else
 #define XQ_CAT2(a, b, c, d) xq_launch_decode_##a##_##b##_##c##d
+#endif
 #define XQ_CAT(a, b, c, d) XQ_CAT2(a, b, c, d)
 
 // One translation unit per (head_dim, group, key bits, value bits); n_rep = query heads per kv head.

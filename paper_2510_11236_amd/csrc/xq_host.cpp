@@ -201,8 +201,9 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 // call.  The plan minimises that over n, with at most XQ_MAX_SPLITS splits.
 // Workgroups of the decode kernel that one CU holds at a time: set by the registers of the
 // kernel variant (n_rep query heads per kv head in the pass; a fused pair doubles the heads).
-int decode_wgs_per_cu(bool matrix, int n_rep, bool fused, int g, int bk, int bv) {
+int decode_wgs_per_cu(int matrix, int n_rep, bool fused, int g, int bk, int bv) {
     const int nv = n_rep * (fused ? 2 : 1);
+    if (matrix == 2 && xq_decode_has_kx(128, g, bk, n_rep, fused)) return nv > 4 || g == 32 ? 2 : 3;
     if (matrix) {
         if (nv <= 2 || (n_rep == 4 && !fused && g == 64 && bk + bv < 4)) return 4;
         return nv <= 4 ? 3 : 2;
@@ -634,7 +635,7 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
                        void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                        int32_t flags, void *hip_stream) {
     if (!range_ok(cache, layer0, n_layers) || !q_f16 || !out_f32 || !dev_workspace) return XQ_ERR_INVALID_ARG;
-    if (flags & ~(XQ_DECODE_PAIR_FUSED | XQ_DECODE_VECTOR_ALU)) return XQ_ERR_INVALID_ARG;
+    if (flags & ~(XQ_DECODE_PAIR_FUSED | XQ_DECODE_VECTOR_ALU | XQ_DECODE_MATRIX_F16)) return XQ_ERR_INVALID_ARG;
     if (((uintptr_t)q_f16 & 3) || ((uintptr_t)out_f32 & 3) || ((uintptr_t)dev_workspace & 15)) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
     const int32_t *row = len_row(cache, layer0);
@@ -713,8 +714,9 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
         const int64_t work_items = (int64_t)(r.fused ? (r.e - r.l) / 2 : r.e - r.l) * c.batch * c.n_kv_heads;
         int wgs_per_cu = 4;
         for (int i = 0; i < n_parts; ++i)
-            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(matrix, parts[i], r.fused != 0, c.group,
-                                                                cache->layers[r.l].bk, cache->layers[r.l].bv));
+            wgs_per_cu = std::min(wgs_per_cu, decode_wgs_per_cu(!matrix ? 0 : (flags & XQ_DECODE_MATRIX_F16) ? 1 : 2, parts[i],
+                                                                r.fused != 0, c.group, cache->layers[r.l].bk,
+                                                                cache->layers[r.l].bv));
         plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &r.n_splits, &r.tps);
         r.ws_off = ws_floats;
         ws_floats += (int64_t)workspace_floats(c, r.e - r.l, r.n_splits);
@@ -747,7 +749,8 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
         a.ws = (float *)dev_workspace + runs[ri].ws_off;
         a.scale_log2e = sm_scale * 1.4426950408889634f;
         a.pg = cache->paging;
-        a.matrix = matrix;
+        // 2-bit keys take the fp8 x fp4 key phase unless the caller keeps everything on the fp16 instruction
+        a.matrix = !matrix ? 0 : (d0.bk == 2 && !(flags & XQ_DECODE_MATRIX_F16)) ? 2 : 1;
         if (!fused)
             for (int x = l; x < e; ++x) {
                 a.reuse_codes |= !cache->layers[x].k_store || !cache->layers[x].v_store;

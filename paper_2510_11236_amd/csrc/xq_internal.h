@@ -136,7 +136,8 @@ struct XqDecodeArgs {
     int32_t rep, q_head0;  // query heads per kv head; first of them that this launch serves (it serves n_rep)
     int32_t reuse_codes;  // some layer of the launch reads another layer's codes (keep them in L2)
     int32_t pair_order;   // ... and the launch is a whole number of sharing groups of this many layers (0: not): deal their workgroups out side by side
-    int32_t matrix;       // multiply-adds on the 4x4x4 matrix instruction (head_dim 128) instead of the vector ALU
+    int32_t matrix;       // 0: multiply-adds on the vector ALU; 1: on the 4x4x4 fp16 matrix instruction (head_dim 128);
+                          // 2: as 1 with the key phase on the 16x16x128 fp8 x fp4 instruction (2-bit keys)
     XqPaging pg;
     int32_t seq_T[XQ_MAX_RAGGED];
 };
@@ -148,6 +149,7 @@ hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv,
 hipError_t xq_launch_merge(const XqDecodeArgs &a, int D, int n_layers, hipStream_t s);
 
 bool xq_decode_can_fuse(int D, int g, int n_rep);
+bool xq_decode_has_kx(int D, int g, int bk, int n_rep, int pair_fused);
 
 struct XqUnpackArgs {
     const char *codes;  // region of the layer that stores them

@@ -30,7 +30,7 @@ def test_every_instantiation(D, g, bk, bv, rep):
         cache.quantize_pack(K.cuda(), V.cuda())
         q = synth.queries(w).cuda()
         # flag 1: the pair in one workgroup (where the shape allows); flag 2: vector-ALU kernels
-        outs = [cache.decode_attention(q, sigma, flags=f) for f in (0, 1, 2, 3)]
+        outs = [cache.decode_attention(q, sigma, flags=f) for f in (0, 1, 2, 3, 4, 5)]
         torch.cuda.synchronize()
         st = tl.oracle_slice(w, K, V, 0, 0)
         tl.check_stored(cache, w, st, 0, 0)

@@ -56,7 +56,7 @@ def test_paged_equals_contiguous(tl, D, g, P, rep, T0, n_app):
         assert flat != sorted(flat)          # the order really is scrambled
     q = synth.queries(w).cuda()
     sigma = 1.0 / np.sqrt(D)
-    for flags in (0, 1, 2, 3):
+    for flags in (0, 1, 2, 3, 4, 5):
         for tps in (0, 1):
             plain.set_tiles_per_split(tps)
             paged.set_tiles_per_split(tps)

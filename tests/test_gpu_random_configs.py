@@ -84,9 +84,9 @@ def test_random_config(seed):
     outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1),
             cache.decode_attention(q, sigma, flags=2 + (seed // 2) % 2)]
     cache.set_tiles_per_split(1 + seed % 3)
-    outs.append(cache.decode_attention(q, sigma, flags=seed % 4))
+    outs.append(cache.decode_attention(q, sigma, flags=seed % 6))
     cache.set_tiles_per_split(4096)       # one split
-    outs.append(cache.decode_attention(q, sigma, flags=(seed // 3) % 4))
+    outs.append(cache.decode_attention(q, sigma, flags=(seed // 3) % 6))
     torch.cuda.synchronize()
     worst = 0.0
     for bi in range(w.batch):
