@@ -34,7 +34,10 @@ def _jobs():
     for G in (32, 64):      # the kernels with the fp8 x fp4 key phase: head_dim 128, 2-bit keys
         for bv in (1, 2):
             jobs.append((f"xq_decode_kx_128_{G}_2{bv}.o", "xq_decode.hip",
-                         ["-DXQ_KX_TU", "-DXQ_D=128", f"-DXQ_G={G}", "-DXQ_BK=2", f"-DXQ_BV={bv}"]))
+                         ["-DXQ_KX_TU", "-DXQ_D=128", f"-DXQ_G={G}", "-DXQ_BK=2", f"-DXQ_BV={bv}",
+                          # matrix results straight into ordinary registers (they are folded by vector
+                          # instructions right away; the accumulator-register form costs a copy per value)
+                          "-mllvm", "-amdgpu-mfma-vgpr-form=1"]))
     return jobs
 
 

@@ -111,6 +111,23 @@ __device__ __forceinline__ uint32_t group_umax(uint32_t v) {  // max over aligne
     return v;
 }
 
+// Reductions over the 16 lanes of a DPP row without the LDS crossbar: lane ^ 1, lane ^ 2 inside the
+// quad, then the mirrored half row (the other quad of the 8) and the mirrored row (the other half).
+__device__ __forceinline__ float row16_sum(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true));  // row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, true));  // row_mirror
+    return v;
+}
+__device__ __forceinline__ uint32_t row16_umax(uint32_t v) {
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, true));
+    return v;
+}
+
 template <int W>
 __device__ __forceinline__ float group_sum(float v) {  // sum over aligned groups of W lanes
 #pragma unroll
@@ -554,7 +571,8 @@ void xq_decode_kernel(XqDecodeArgs a) {
                     uint32_t hm = 0;
 #pragma unroll
                     for (int k = 0; k < 8; ++k) hm = max(hm, kmeta[y][k / 4][k % 4] & 0x7fffu);
-                    hm = group_umax<LPG>(hm);
+                    hm = row16_umax(hm);
+                    if constexpr (LPG == 32) hm = max(hm, (uint32_t)__shfl_xor((int)hm, 16, 64));
                     const int es = max((int)(hm >> 10), 1) - 14;  // 2^es > every scale of the group
 #pragma unroll
                     for (int x = 0; x < NPH; ++x) {
@@ -596,7 +614,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
                         float qs = qsc[0];
 #pragma unroll
                         for (int u = 1; u < NV; ++u) qs = (u == v) ? qsc[u] : qs;
-                        const float zmine = group_sum<16>(zp) * qs;
+                        const float zmine = row16_sum(zp) * qs;
                         if constexpr (HP == 2 && NREP >= 2) {
                             const float zother = __shfl_xor(zmine, 16, 64);
                             zs[y * NREP + 2 * x] = hp == 0 ? zmine : zother;
@@ -756,31 +774,24 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 }
                 xs[px][pm] = fmaf(fmaf(fmaf(pc[3], 0.0625f, pc[2]), 0.0625f, pc[1]), 0.0625f, pc[0]);
                 // xs[x][m] = score of (token 16 m + r16, head 4 x + row); wanted: lane (r16, row) holds tokens
-                // 32 row + 16 s + r16 for every head.  A 4 x 4 transpose over the lanes 16 apart in two
-                // rounds of swaps: column blocks 4..7 go to the upper half wave, then 2..3 (6..7) to the odd rows.
+                // 32 row + 16 s + r16 for every head: a 4 x 4 transpose over the lanes 16 apart, through the
+                // wave's A table space (all its readers are done), rows [token r16][head][column block]
+                // padded to 36 floats per head set.
+                float *tp = (float *)&s_kx[wave][0][0][0];
+                wave_lds_fence();
 #pragma unroll
                 for (int x = 0; x < NSET; ++x) {
-#pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(xs[x][m]), __float_as_uint(xs[x][m + 4]), false, false);
-                        xs[x][m] = __uint_as_float(r[0]);      // heads 0, 1 (by row % 2) of blocks 0..3 | 4..7
-                        xs[x][m + 4] = __uint_as_float(r[1]);  // heads 2, 3
-                    }
-#pragma unroll
-                    for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-                        for (int s2 = 0; s2 < 2; ++s2) {
-                            if (4 * x + 2 * hh >= NV) continue;
-                            const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(xs[x][4 * hh + s2]),
-                                                                            __float_as_uint(xs[x][4 * hh + s2 + 2]), false, false);
-                            xs[x][4 * hh + s2] = __uint_as_float(r[0]);      // head 2 hh
-                            xs[x][4 * hh + s2 + 2] = __uint_as_float(r[1]);  // head 2 hh + 1
-                        }
+                    float *dst = tp + ((x * 16 + r16) * 36 + row * 8);
+                    *(float4 *)dst = make_float4(xs[x][0], xs[x][1], xs[x][2], xs[x][3]);
+                    *(float4 *)(dst + 4) = make_float4(xs[x][4], xs[x][5], xs[x][6], xs[x][7]);
                 }
+                wave_lds_fence();
 #pragma unroll
-                for (int v = 0; v < NV; ++v)
-#pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) tsum[s2][v] = xs[v / 4][4 * ((v % 4) / 2) + 2 * (v % 2) + s2] * fac[v];
+                for (int v = 0; v < NV; ++v) {
+                    const float2 t2 = *(const float2 *)(tp + (((v / 4) * 16 + r16) * 36 + (v % 4) * 8 + 2 * row));
+                    tsum[0][v] = t2.x * fac[v];
+                    tsum[1][v] = t2.y * fac[v];
+                }
             } else if constexpr (MM) {
                 // the lanes of a token group are the lanes that prepared it (kg == gi); A matrix n
                 // sits in block n % NB of register pair n / NB
