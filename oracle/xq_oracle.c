@@ -22,6 +22,8 @@
  *   xqo_attention       softmax(sigma q K^T) V over the dequantized cache plus
  *                       the fp16 residual rows (the textbook definition; the
  *                       paper dequantizes and then calls ordinary attention).
+ *   xqo_prefill_attention_row  causal attention of the prompt on its fp16 K/V (the
+ *                       paper is silent on it: textbook definition).
  *   xqo_pack_k/_v_words bit layout of the packed code words.  The layout is
  *                       this build's, not the paper's: parity unpinned by the
  *                       paper; it is pinned by the written specification in
@@ -208,6 +210,35 @@ void xqo_attention(const uint16_t *q, const double *Kh, const double *Vh, int T,
     for (int d = 0; d < D; ++d) {
         double acc = 0.0;
         for (int t = 0; t < T; ++t) acc += u[t] * Vh[(long)t * D + d];
+        out[d] = (float)(acc / denom);
+    }
+    free(u);
+}
+
+/* ------------------------------------------------------- prefill (causal) attention
+ * The paper's procedure quantizes the prompt's K/V (Appendix Alg. 1, first loop) and reads the
+ * quantized cache from the first decode step on (second loop); the attention of the prompt itself
+ * is not described, so it is taken to be the ordinary causal attention of the model on the fp16
+ * K/V it has just computed: query t attends to keys 0..t,
+ *   o_t = softmax(sigma q_t K_{0..t}^T) V_{0..t}.
+ * One query row per call (q: fp16 [D]; K, V: fp16 [T][D] with T > t); out: fp32 [D]. */
+void xqo_prefill_attention_row(const uint16_t *q, const uint16_t *K, const uint16_t *V, int t, int D,
+                               double sigma, float *out) {
+    int n = t + 1;
+    double *u = (double *)malloc(sizeof(double) * (size_t)n);
+    double m = -INFINITY;
+    for (int j = 0; j < n; ++j) {
+        double acc = 0.0;
+        for (int d = 0; d < D; ++d)
+            acc += (double)xqo_half_to_float(q[d]) * (double)xqo_half_to_float(K[(long)j * D + d]);
+        u[j] = sigma * acc;
+        if (u[j] > m) m = u[j];
+    }
+    double denom = 0.0;
+    for (int j = 0; j < n; ++j) { u[j] = exp(u[j] - m); denom += u[j]; }
+    for (int d = 0; d < D; ++d) {
+        double acc = 0.0;
+        for (int j = 0; j < n; ++j) acc += u[j] * (double)xqo_half_to_float(V[(long)j * D + d]);
         out[d] = (float)(acc / denom);
     }
     free(u);

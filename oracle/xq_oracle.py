@@ -45,6 +45,8 @@ def lib():
         L.xqo_half_rows_to_double.argtypes = [u16p, C.c_long, f64p]
         L.xqo_attention.restype = None
         L.xqo_attention.argtypes = [u16p, f64p, f64p, C.c_int, C.c_int, C.c_double, f32p]
+        L.xqo_prefill_attention_row.restype = None
+        L.xqo_prefill_attention_row.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_double, f32p]
         for f in (L.xqo_pack_k_words, L.xqo_pack_v_words):
             f.restype = None
             f.argtypes = [u8p, C.c_int, C.c_int, C.c_int, u32p]
@@ -162,6 +164,19 @@ def attention(q, Kh, Vh, sigma):
     out = np.zeros(D, np.float32)
     lib().xqo_attention(_p(q, C.c_uint16), _p(Kh, C.c_double), _p(Vh, C.c_double), T, D, float(sigma),
                         _p(out, C.c_float))
+    return out
+
+
+def prefill_attention(q, K, V, sigma, rows=None):
+    """Causal attention of a prompt on its own fp16 K/V: q, K, V [T][D] fp16; query t sees keys
+    0..t.  rows: the query positions to compute (default all) -> [len(rows)][D] float32."""
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    T, D = K.shape
+    rows = range(T) if rows is None else rows
+    out = np.zeros((len(rows), D), np.float32)
+    for i, t in enumerate(rows):
+        lib().xqo_prefill_attention_row(_p(q[t], C.c_uint16), _p(K, C.c_uint16), _p(V, C.c_uint16), int(t), D,
+                                        float(sigma), _p(out[i], C.c_float))
     return out
 
 

@@ -34,6 +34,10 @@ MUTANTS = [
     (C_FILE, "acc += u[t] * Vh[(long)t * D + d];", "acc += u[t] * Vh[(long)t * D + (D - 1 - d)];"),  # output channels mirrored
     (C_FILE, "acc += (double)xqo_half_to_float(q[d]) * Kh[(long)t * D + d];",
      "acc += (double)xqo_half_to_float(q[d]) * Kh[(long)t * D + (d ^ 1)];"),            # q . K with channels swapped in pairs
+    (C_FILE, "int n = t + 1;", "int n = t;"),                                           # a prompt token does not see itself
+    (C_FILE, "u[j] = sigma * acc;", "u[j] = acc;"),                                      # prefill softmax scale dropped
+    (C_FILE, "acc += u[j] * (double)xqo_half_to_float(V[(long)j * D + d]);",
+     "acc += u[j] * (double)xqo_half_to_float(V[(long)j * D + (D - 1 - d)]);"),          # prefill output channels mirrored
     (C_FILE, "int wi = d / per, bit = B * (d % per);", "int wi = d / per, bit = B * (per - 1 - d % per);"),  # MSB-first key words
     (C_FILE, "int slot = d / CPL, e = (t % 32) * CPL + d % CPL;", "int slot = d / CPL, e = (d % CPL) * 32 + (t % 32);"),  # value order inside a slot
     (C_FILE, "if (l < m || l % 2 == 0) bits +=", "if (l < m || l % 2 == 1) bits +="),    # second layer of a pair charged

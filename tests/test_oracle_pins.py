@@ -507,6 +507,40 @@ def test_attention_invariants(oracle):
     assert np.allclose(oracle.attention(q, Kd, Vh, 1.0), Vh[13], atol=1e-6)
 
 
+# ------------------------------------------------- prefill (causal) attention
+def test_prefill_attention_is_textbook_causal(oracle):
+    """The prompt's own attention: against torch.softmax with a causal mask, against the (separately
+    pinned) one-query attention on the visible prefix, and the properties that define causality."""
+    import torch
+    rng = np.random.default_rng(21)
+    T, D, sigma = 37, 16, 0.31
+    q = rng.standard_normal((T, D)).astype(np.float16)
+    K = rng.standard_normal((T, D)).astype(np.float16)
+    V = rng.standard_normal((T, D)).astype(np.float16)
+    got = oracle.prefill_attention(q, K, V, sigma)
+    tq, tk, tv = (torch.from_numpy(a.astype(np.float64)) for a in (q, K, V))
+    scores = (tq @ tk.T) * sigma
+    scores = scores.masked_fill(torch.triu(torch.ones(T, T, dtype=torch.bool), diagonal=1), float("-inf"))
+    ref = torch.softmax(scores, dim=-1) @ tv
+    assert np.allclose(got, ref.numpy(), rtol=0, atol=1e-6)
+    # row t = ordinary attention of q_t over the first t + 1 tokens (that routine has pins of its own)
+    for t in (0, 1, 17, T - 1):
+        one = oracle.attention(q[t], K[:t + 1].astype(np.float64), V[:t + 1].astype(np.float64), sigma)
+        assert np.allclose(got[t], one, rtol=0, atol=1e-6)
+    assert np.allclose(got[0], V[0].astype(np.float32), atol=1e-6)              # the first token sees only itself
+    # later tokens are invisible: changing them leaves earlier rows as they are, bit for bit
+    K2, V2 = K.copy(), V.copy()
+    K2[20:] = rng.standard_normal((T - 20, D)).astype(np.float16)
+    V2[20:] = 7.0
+    again = oracle.prefill_attention(q, K2, V2, sigma, rows=range(20))
+    assert np.array_equal(again, got[:20])
+    assert not np.allclose(oracle.prefill_attention(q, K2, V2, sigma, rows=[20])[0], got[20], atol=1e-3)
+    # zero queries average the visible values
+    zero = oracle.prefill_attention(np.zeros((T, D), np.float16), K, V, sigma, rows=[0, 5, T - 1])
+    for i, t in enumerate((0, 5, T - 1)):
+        assert np.allclose(zero[i], V[:t + 1].astype(np.float64).mean(0), atol=1e-6)
+
+
 # ----------------------------------------------------------------- pack layout
 def _unpack_k_spec(words, Tq, D, B):
     """Reader written from the layout text in include/xq.h (not from the oracle)."""
