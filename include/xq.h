@@ -163,6 +163,23 @@ int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int3
                          const void *k_f16, const void *v_f16, const int64_t strides[4], int32_t T,
                          void *hip_stream);
 
+/* Prefill with the pack inside the prompt's own attention kernel (head_dim 128): computes the
+ * causal attention of the T prompt tokens of layers [layer0, layer0 + n_layers),
+ *   out[l, i, hq, t] = softmax_{j <= t}(sm_scale q[l, i, hq, t] . k[l, i, hkv, j]) v[l, i, hkv, j],
+ * hkv = hq / (n_q_heads / n_kv_heads), on the fp16 K/V (the paper's procedure reads the quantized
+ * cache from the first decode step on; the prompt's attention is the model's ordinary one), and
+ * quantizes and packs those K/V exactly as xq_quantize_pack does (same stored bytes, same state
+ * afterwards): the workgroup whose queries are the tokens of a 128-token block packs that block,
+ * so that K and V come from HBM once instead of twice.
+ * q_f16: device fp16 [n_layers][batch][n_q_heads][T][128], contiguous; out_f32: device fp32, same
+ * shape; k_f16, v_f16, strides, T: as for xq_quantize_pack (all sequences, empty layers).
+ * flags: 0, or XQ_PREFILL_NO_PACK for the attention alone (the cache is not touched).
+ * XQ_ERR_UNSUPPORTED for head_dim 64 and, when packing, for caches with merged pair codes. */
+#define XQ_PREFILL_NO_PACK 1
+int xq_prefill_attention_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16, const void *k_f16,
+                              const void *v_f16, const int64_t strides[4], void *out_f32, float sm_scale, int32_t T,
+                              int32_t flags, void *hip_stream);
+
 /* Decode-time append of one token per sequence to layers [layer0, layer0 + n_layers).
  * k_new_f16, v_new_f16: device fp16 [n_layers][batch][n_kv_heads][D], contiguous.
  * A sequence whose ring is full first has its oldest g tokens quantized and packed (same

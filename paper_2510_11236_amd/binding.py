@@ -57,6 +57,9 @@ def lib():
         L.xq_cache_pages.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
         L.xq_cache_free_pages.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xq_append_token.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
+        L.xq_prefill_attention_pack.restype = C.c_int
+        L.xq_prefill_attention_pack.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp, C.POINTER(C.c_int64), vp, C.c_float,
+                                                C.c_int32, C.c_int32, vp]
         L.xq_decode_attention.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, vp, C.c_size_t, C.c_int32, vp]
         L.xq_decode_attention_static.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_float, C.c_int32, vp]
         L.xq_decode_attention_static.restype = C.c_int
@@ -190,6 +193,22 @@ class XqCache:
         _check(lib().xq_quantize_pack_seq(self._h, layer0, k.shape[0], seq0, k.shape[1], C.c_void_p(k.data_ptr()),
                                           C.c_void_p(v.data_ptr()), strides, k.shape[3], _stream()),
                "xq_quantize_pack_seq")
+
+    def prefill_attention_pack(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, sm_scale: float,
+                               out: torch.Tensor = None, layer0=0, pack=True):
+        """Causal attention of the prompt + quantize/pack of its K/V in one pass.  q: fp16 contiguous
+        [n_layers][b][h_q][T][128]; k, v as for quantize_pack -> fp32 [n_layers][b][h_q][T][128]."""
+        assert q.is_contiguous() and q.dtype == torch.float16 and q.dim() == 5
+        assert k.dtype == torch.float16 and v.dtype == torch.float16 and k.dim() == 5 and k.shape == v.shape
+        assert k.stride() == v.stride() and k.stride(4) == 1 and k.is_cuda and q.shape[3] == k.shape[3]
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        assert out.is_contiguous() and out.dtype == torch.float32 and out.shape == q.shape
+        strides = (C.c_int64 * 4)(*k.stride()[:4])
+        _check(lib().xq_prefill_attention_pack(self._h, layer0, k.shape[0], C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+                                               C.c_void_p(v.data_ptr()), strides, C.c_void_p(out.data_ptr()), float(sm_scale),
+                                               k.shape[3], 0 if pack else 1, _stream()), "xq_prefill_attention_pack")
+        return out
 
     def append_token(self, k_new: torch.Tensor, v_new: torch.Tensor, layer0=0):
         """k_new, v_new: fp16 contiguous [n_layers][b][h_kv][D]."""

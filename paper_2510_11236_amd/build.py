@@ -24,6 +24,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.
 def _jobs():
     jobs = [("xq_host.o", "xq_host.cpp", ["-x", "hip", "-ffp-contract=off"]),
             ("xq_pack.o", "xq_pack.hip", ["-ffp-contract=off"]),
+            ("xq_prefill.o", "xq_prefill.hip", ["-ffp-contract=off"]),
             ("xq_merge.o", "xq_merge.hip", [])]
     for D in (128, 64):
         for G in (32, 64):

@@ -535,6 +535,87 @@ int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int3
     return XQ_OK;
 }
 
+int xq_prefill_attention_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16, const void *k_f16,
+                              const void *v_f16, const int64_t strides[4], void *out_f32, float sm_scale, int32_t T,
+                              int32_t flags, void *hip_stream) {
+    if (!range_ok(cache, layer0, n_layers) || !q_f16 || !k_f16 || !v_f16 || !out_f32 || !strides || T < 1)
+        return XQ_ERR_INVALID_ARG;
+    if (flags & ~XQ_PREFILL_NO_PACK) return XQ_ERR_INVALID_ARG;
+    const xq_config &c = cache->cfg;
+    if (c.head_dim != 128) return XQ_ERR_UNSUPPORTED;
+    const bool pack = !(flags & XQ_PREFILL_NO_PACK);
+    if (pack && c.merge_mode != XQ_MERGE_NONE) return XQ_ERR_UNSUPPORTED;  // merged codes need two layers' tiles at once
+    if (pack && T > c.max_tokens) return XQ_ERR_CAPACITY;
+    if ((int64_t)c.batch * c.n_q_heads > 65535) return XQ_ERR_UNSUPPORTED;
+    for (int i = 0; i < 4; ++i)
+        if (strides[i] < 0 || strides[i] % 8) return XQ_ERR_INVALID_ARG;
+    if (strides[3] < c.head_dim || ((uintptr_t)k_f16 & 15) || ((uintptr_t)v_f16 & 15) || ((uintptr_t)q_f16 & 15) ||
+        ((uintptr_t)out_f32 & 15))
+        return XQ_ERR_INVALID_ARG;
+    if (pack)
+        for (int l = layer0; l < layer0 + n_layers; ++l)
+            for (int i = 0; i < c.batch; ++i)
+                if (len_row(cache, l)[i] != 0) return XQ_ERR_STATE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int Tq = pack ? xq_quantized_len(T, c.group, c.residual) : 0;
+    if (pack && cache->paging.table && Tq > 0) {
+        std::vector<int32_t> want(c.batch, Tq);
+        if (pages_missing(cache, 0, c.batch, want.data()) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
+        int rc = take_pages(cache, 0, c.batch, want.data(), s);
+        if (rc) return rc;
+    }
+    XqPrefillArgs a;
+    memset(&a, 0, sizeof(a));
+    a.pk.arena = cache->arena;
+    a.pk.layers = cache->dev_layers;
+    a.pk.st = cache->strides;
+    a.pk.layer0 = layer0;
+    a.pk.batch = c.batch;
+    a.pk.n_kv_heads = c.n_kv_heads;
+    a.pk.R = c.residual;
+    a.pk.k_src = (const uint16_t *)k_f16;
+    a.pk.v_src = (const uint16_t *)v_f16;
+    a.pk.s_layer = strides[0];
+    a.pk.s_batch = strides[1];
+    a.pk.s_head = strides[2];
+    a.pk.s_tok = strides[3];
+    a.pk.pg = cache->paging;
+    a.pk.n_groups = Tq / c.group;
+    fill_pack_consts(c, a.pk);
+    a.q = (const uint16_t *)q_f16;
+    a.out = (float *)out_f32;
+    a.T = T;
+    a.Tq = Tq;
+    a.batch = c.batch;
+    a.n_q_heads = c.n_q_heads;
+    a.scale_log2e = sm_scale * 1.4426950408889634f;
+    if (xq_launch_prefill(a, c.group, n_layers, pack ? 1 : 0, s) != hipSuccess) return XQ_ERR_HIP;
+    if (!pack) return XQ_OK;
+    XqRingArgs r;
+    memset(&r, 0, sizeof(r));
+    r.arena = cache->arena;
+    r.layers = cache->dev_layers;
+    r.st = cache->strides;
+    r.layer0 = layer0;
+    r.batch = c.batch;
+    r.n_kv_heads = c.n_kv_heads;
+    r.R = c.residual;
+    r.D = c.head_dim;
+    r.k_src = (const uint16_t *)k_f16;
+    r.v_src = (const uint16_t *)v_f16;
+    r.s_layer = strides[0];
+    r.s_batch = strides[1];
+    r.s_head = strides[2];
+    r.s_tok = strides[3];
+    r.src_tok0 = Tq;
+    r.dst_tok0 = Tq;
+    r.n_tok = T - Tq;
+    if (xq_launch_ring_write(r, n_layers, s) != hipSuccess) return XQ_ERR_HIP;
+    for (int l = layer0; l < layer0 + n_layers; ++l)
+        for (int i = 0; i < c.batch; ++i) len_row(cache, l)[i] = T;
+    return XQ_OK;
+}
+
 int xq_quantize_pack(xq_cache *cache, int32_t layer0, int32_t n_layers, const void *k_f16,
                      const void *v_f16, const int64_t strides[4], int32_t T, void *hip_stream) {
     if (!cache) return XQ_ERR_INVALID_ARG;

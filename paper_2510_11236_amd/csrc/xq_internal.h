@@ -102,6 +102,18 @@ struct XqPackArgs {
 };
 hipError_t xq_launch_pack(const XqPackArgs &a, int D, int g, int n_layers, hipStream_t s);
 
+// Causal attention of a prompt (head_dim 128) with the pack of its K/V in the same kernel: pk describes
+// the K/V source and the pack exactly as for xq_launch_pack (from_ring = 0, all sequences).
+struct XqPrefillArgs {
+    XqPackArgs pk;
+    const uint16_t *q;   // [n_layers][b][h_q][T][128] fp16
+    float *out;          // same shape, fp32
+    int32_t T, Tq;       // prompt length; tokens of it that are packed
+    int32_t batch, n_q_heads;
+    float scale_log2e;   // sm_scale * log2(e)
+};
+hipError_t xq_launch_prefill(const XqPrefillArgs &a, int g, int n_layers, int pack, hipStream_t s);
+
 struct XqRingArgs {
     char *arena;
     const XqLayerDesc *layers;
