@@ -214,6 +214,18 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * the key weights travel as four fp8 terms, 16 significant bits).  XQ_DECODE_MATRIX_F16 keeps the
  * keys on the 4x4x4 fp16 instruction like the values (1-bit keys always are).  Same error bound. */
 #define XQ_DECODE_MATRIX_F16 4
+/* Who merges the split partials (per-split running maximum, denominator and output).  Either a
+ * merge launch that follows the decode launch, or the decode launch itself: the workgroups of a
+ * (layer, sequence, kv head) count themselves in on a counter in the cache's arena and the last to
+ * arrive merges.  Both sum in the same fixed order: same results bit for bit.  By default the library
+ * chooses (the decode launch merges when it is brief: a single round of workgroups of at most 8 tiles,
+ * as in a call for one layer of a short cache, where a second launch's fixed cost shows).
+ * XQ_DECODE_MERGE_LAUNCH forces the merge launch, XQ_DECODE_MERGE_IN_LAUNCH the other (both:
+ * XQ_ERR_INVALID_ARG).  Because of the counters, two decode calls on one cache that may merge in the
+ * decode launch must not overlap in time on the GPU (calls on one stream never do); calls with
+ * XQ_DECODE_MERGE_LAUNCH touch no counter and may overlap when their workspaces differ. */
+#define XQ_DECODE_MERGE_LAUNCH 8
+#define XQ_DECODE_MERGE_IN_LAUNCH 16
 int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
                         void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                         int32_t flags, void *hip_stream);

@@ -17,6 +17,8 @@ _LIB = None
 XQ_DECODE_PAIR_FUSED = 1
 XQ_DECODE_VECTOR_ALU = 2
 XQ_DECODE_MATRIX_F16 = 4
+XQ_DECODE_MERGE_LAUNCH = 8
+XQ_DECODE_MERGE_IN_LAUNCH = 16
 
 
 class XqError(RuntimeError):

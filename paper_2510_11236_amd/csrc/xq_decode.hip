@@ -362,49 +362,6 @@ void xq_decode_kernel(XqDecodeArgs a) {
         // with few heads a second, pre-shifted copy of q saves a multiply per weight
         constexpr bool QK_COPY = NV == 1;
         float qk[QK_COPY ? NV : 1][CPP];
-        if constexpr (MM) {
-            // scaled queries in the order the A matrices take their channels: matrix n, element k
-            for (int idx = tid; idx < NV * D; idx += 256) {
-                const int v = idx / D, pos = idx % D, n = pos / 4, k = pos % 4;
-                const int ci = n / 2, p = 2 * (n % 2) + k / 2;
-                const int ch = KX ? pos  // (the fp8 x fp4 path reads its channels in natural order)
-                                  : (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4 + p + (k % 2) * HALFK;
-                s_q[v][pos] = hbits(qptr(v)[ch]) * a.scale_log2e;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const float mx = wave_max(fmaxf(fabsf(s_q[v][lane]), fabsf(s_q[v][lane + 64])));
-                int e = (int)((__float_as_uint(mx) >> 23) & 0xffu) - 126;  // 2^e > |q| of every channel
-                e = __builtin_amdgcn_readfirstlane(min(max(e, -40), 60));
-                eq[v] = e;
-                qsc[v] = __uint_as_float((uint32_t)(127 - QE + e) << 23);  // 2^(e - QE)
-            }
-            // the table keeps q 2^(14 - e): weights come out in fp16 range without a multiply per
-            // channel, and the zero-point sum is scaled back once per head
-            __syncthreads();
-            for (int idx = tid; idx < NV * D; idx += 256) {
-                const int v = idx / D;
-                float f = 1.0f;
-#pragma unroll
-                for (int u = 0; u < NV; ++u) f = (u == v) ? __uint_as_float((uint32_t)(127 + QE - eq[u]) << 23) : f;
-                s_q[v][idx % D] *= f;
-            }
-            __syncthreads();
-        } else if constexpr (Q_LDS) {
-            for (int idx = tid; idx < NV * D; idx += 256) s_q[idx / D][idx % D] = hbits(qptr(idx / D)[idx % D]) * a.scale_log2e;
-            __syncthreads();
-        } else {
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const uint16_t *qp = qptr(v);
-#pragma unroll
-                for (int k = 0; k < CPP; ++k) {
-                    qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
-                    if constexpr (QK_COPY) qk[v][k] = qz[v][k] * pw[k];
-                }
-            }
-        }
         // Every workgroup starts at a different tile of its range (and wraps around): slices lie
         // at large power-of-two strides, so workgroups marching in step from tile 0 would all
         // hit the same memory channels at once.  Softmax accumulation does not care about order.
@@ -537,6 +494,51 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 if constexpr (PIPE_KMETA) load_kmeta(t);
                 load_kcodes(t);
                 load_values(t);
+            }
+        }
+        // ---- the queries (after the first tile's loads are under way: one memory latency, not two,
+        // before the first tile can start -- a one-layer call is little more than that latency)
+        if constexpr (MM) {
+            // scaled queries in the order the A matrices take their channels: matrix n, element k
+            for (int idx = tid; idx < NV * D; idx += 256) {
+                const int v = idx / D, pos = idx % D, n = pos / 4, k = pos % 4;
+                const int ci = n / 2, p = 2 * (n % 2) + k / 2;
+                const int ch = KX ? pos  // (the fp8 x fp4 path reads its channels in natural order)
+                                  : (ci / (2 * CPB)) * PERK + ((ci / CPB) % 2) * BYTEK + (ci % CPB) * 4 + p + (k % 2) * HALFK;
+                s_q[v][pos] = hbits(qptr(v)[ch]) * a.scale_log2e;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const float mx = wave_max(fmaxf(fabsf(s_q[v][lane]), fabsf(s_q[v][lane + 64])));
+                int e = (int)((__float_as_uint(mx) >> 23) & 0xffu) - 126;  // 2^e > |q| of every channel
+                e = __builtin_amdgcn_readfirstlane(min(max(e, -40), 60));
+                eq[v] = e;
+                qsc[v] = __uint_as_float((uint32_t)(127 - QE + e) << 23);  // 2^(e - QE)
+            }
+            // the table keeps q 2^(14 - e): weights come out in fp16 range without a multiply per
+            // channel, and the zero-point sum is scaled back once per head
+            __syncthreads();
+            for (int idx = tid; idx < NV * D; idx += 256) {
+                const int v = idx / D;
+                float f = 1.0f;
+#pragma unroll
+                for (int u = 0; u < NV; ++u) f = (u == v) ? __uint_as_float((uint32_t)(127 + QE - eq[u]) << 23) : f;
+                s_q[v][idx % D] *= f;
+            }
+            __syncthreads();
+        } else if constexpr (Q_LDS) {
+            for (int idx = tid; idx < NV * D; idx += 256) s_q[idx / D][idx % D] = hbits(qptr(idx / D)[idx % D]) * a.scale_log2e;
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const uint16_t *qp = qptr(v);
+#pragma unroll
+                for (int k = 0; k < CPP; ++k) {
+                    qz[v][k] = hbits(qp[li * CPP + k]) * a.scale_log2e;
+                    if constexpr (QK_COPY) qk[v][k] = qz[v][k] * pw[k];
+                }
             }
         }
         // One tile of the wave.  more: the wave has a further tile, whose register sets are reloaded
@@ -1176,8 +1178,36 @@ void xq_decode_kernel(XqDecodeArgs a) {
         const int y = v / NREP, n = v % NREP;
         float *wp = a.ws + ((((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * a.rep + a.q_head0 + n) *
                                 (a.n_splits + 1) + split) * (D + 2);
-        wp[e] = val;
+        // (device-scope store: written through the L2 of this XCD, for a reader on another)
+        if (a.arrivals) __hip_atomic_store(wp + e, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else wp[e] = val;
     }
+    if (a.arrivals == nullptr) return;  // a merge launch follows
+    // ---------------------------------------------------------------- the last workgroup to arrive merges
+    // The n_splits + 1 workgroups of this (layer or pair, sequence, kv head) count themselves in
+    // once their partials have been written; whoever finds the count complete reads all of them
+    // back and writes the outputs, in the merge kernel's order and arithmetic.  Nobody waits: the
+    // others simply leave.  The counter is back at zero for the next launch.
+    // Ordering without cache-wide write-backs or invalidations (a device-scope fence costs an L2
+    // sweep per workgroup here and halves the kernel's speed): the partials are device-scope
+    // stores, the barrier below waits until the memory system has acknowledged every one of them
+    // (s_waitcnt vmcnt(0) before s_barrier), only then does thread 0 count the workgroup in with a
+    // device-scope atomic; the last arrival's loads are device-scope loads issued after its own
+    // atomic has returned.
+    __shared__ uint32_t s_last;
+    __syncthreads();
+    uint32_t *arrive = a.arrivals + (int64_t)lz * nbh + bh;
+    if (tid == 0) s_last = __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)a.n_splits;
+    __syncthreads();
+    if (!s_last) return;
+    static_assert(sizeof(s_raw) >= sizeof(float) * XQ_MERGE_LDS_FLOATS(NV), "merge scratch");
+    xq_merge_block<D, NV, true>(
+        [&](int v) -> int64_t {
+            const int y = v / NREP, n = v % NREP;
+            return ((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * a.rep + a.q_head0 + n;
+        },
+        a.ws, a.out, a.n_splits + 1, (float *)s_raw, tid);
+    if (tid == 0) *arrive = 0;
 }
 
 template <int NREP>

@@ -119,6 +119,8 @@ struct Carve {
     XqStrides st;
     int64_t total;
     int64_t page_table;  // byte offset of the device page table (paged caches)
+    int64_t arrivals;    // byte offset and size of the decode launches' arrival counters
+    int64_t arrivals_bytes;
     int32_t max_pages;   // its width: pages a sequence can hold
 };
 
@@ -142,6 +144,9 @@ Carve carve(const xq_config &c, XqLayerDesc *descs) {
     r.max_pages = paged ? (int32_t)((maxTq + c.page_tokens - 1) / c.page_tokens) : 0;
     r.page_table = off;
     if (paged) off = align256(off + (int64_t)c.batch * (r.max_pages > 0 ? r.max_pages : 1) * 4);
+    r.arrivals = off;
+    r.arrivals_bytes = (int64_t)c.n_layers * nbh * 4;
+    off = align256(off + r.arrivals_bytes);
     for (int l = 0; l < c.n_layers; ++l) {
         XqLayerDesc d;
         d.bk = bits_of(c, l, false);
@@ -308,7 +313,9 @@ int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, x
         c->pages_used.assign(cfg->batch, 0);
         for (int p = cfg->n_pages - 1; p >= 0; --p) c->free_pages.push_back(p);  // page 0 is handed out first
     }
-    if (hipMemcpy(c->dev_layers, c->layers, sizeof(XqLayerDesc) * cfg->n_layers, hipMemcpyHostToDevice) != hipSuccess) {
+    c->arrivals = (uint32_t *)(c->arena + cv.arrivals);
+    if (hipMemcpy(c->dev_layers, c->layers, sizeof(XqLayerDesc) * cfg->n_layers, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemset(c->arrivals, 0, (size_t)cv.arrivals_bytes) != hipSuccess) {
         delete c;
         return XQ_ERR_HIP;
     }
@@ -716,7 +723,10 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
                        void *out_f32, float sm_scale, void *dev_workspace, size_t workspace_bytes,
                        int32_t flags, void *hip_stream) {
     if (!range_ok(cache, layer0, n_layers) || !q_f16 || !out_f32 || !dev_workspace) return XQ_ERR_INVALID_ARG;
-    if (flags & ~(XQ_DECODE_PAIR_FUSED | XQ_DECODE_VECTOR_ALU | XQ_DECODE_MATRIX_F16)) return XQ_ERR_INVALID_ARG;
+    if (flags & ~(XQ_DECODE_PAIR_FUSED | XQ_DECODE_VECTOR_ALU | XQ_DECODE_MATRIX_F16 | XQ_DECODE_MERGE_LAUNCH |
+                  XQ_DECODE_MERGE_IN_LAUNCH))
+        return XQ_ERR_INVALID_ARG;
+    if ((flags & XQ_DECODE_MERGE_LAUNCH) && (flags & XQ_DECODE_MERGE_IN_LAUNCH)) return XQ_ERR_INVALID_ARG;
     if (((uintptr_t)q_f16 & 3) || ((uintptr_t)out_f32 & 3) || ((uintptr_t)dev_workspace & 15)) return XQ_ERR_INVALID_ARG;
     const xq_config &c = cache->cfg;
     const int32_t *row = len_row(cache, layer0);
@@ -764,6 +774,7 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
     struct Run {
         int l, e, fused;
         int n_splits, tps;  // each run is a launch of its own and gets its own split plan
+        bool brief;         // one round of workgroups of at most 8 tiles each: a launch of a few microseconds
         int64_t ws_off;     // where its partials start in the workspace, in floats
     };
     Run runs[XQ_MAX_LAYERS];
@@ -783,7 +794,7 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
                 e += 1;
             }
         }
-        runs[n_runs++] = Run{l, e, fused, 0, 0, 0};
+        runs[n_runs++] = Run{l, e, fused, 0, 0, false, 0};
         l = e;
     }
     const bool matrix = c.head_dim == 128 && !(flags & XQ_DECODE_VECTOR_ALU);
@@ -799,6 +810,7 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
                                                                 r.fused != 0, c.group, cache->layers[r.l].bk,
                                                                 cache->layers[r.l].bv));
         plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &r.n_splits, &r.tps);
+        r.brief = r.tps <= 8 && work_items * (r.n_splits + 1) <= 256 * wgs_per_cu;
         r.ws_off = ws_floats;
         ws_floats += (int64_t)workspace_floats(c, r.e - r.l, r.n_splits);
     }
@@ -839,12 +851,18 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
         // the run is a whole number of sharing groups (pairs by default), some of which share codes
         a.pair_order = (a.reuse_codes && l % group_size(c) == 0 && (e - l) % group_size(c) == 0) ? group_size(c) : 0;
         a.rep = rep;
+        // Who merges the split partials: the last workgroup to arrive, or a launch of its own.  Measured,
+        // the first wins only where a second launch's fixed cost shows (one layer of a 4k-token cache:
+        // 12.9 against 13.4 us per call); on long launches its round trips to memory at the tail cost as
+        // much as the launch they save (one layer of the 32k GQA cache: 3 % slower).
+        const bool in_launch = (flags & XQ_DECODE_MERGE_IN_LAUNCH) || (!(flags & XQ_DECODE_MERGE_LAUNCH) && runs[ri].brief);
+        a.arrivals = in_launch ? cache->arrivals : nullptr;
         for (int i = 0; i < n_parts; ++i) {
             if (xq_launch_decode(a, c.head_dim, c.group, d0.bk, d0.bv, parts[i], e - l, fused, s) != hipSuccess)
                 return XQ_ERR_HIP;
             a.q_head0 += parts[i];
         }
-        if (xq_launch_merge(a, c.head_dim, e - l, s) != hipSuccess) return XQ_ERR_HIP;
+        if (!a.arrivals && xq_launch_merge(a, c.head_dim, e - l, s) != hipSuccess) return XQ_ERR_HIP;
     }
     return XQ_OK;
 }

@@ -60,6 +60,7 @@ struct xq_cache {
     size_t arena_bytes;
     XqLayerDesc layers[XQ_MAX_LAYERS];
     XqLayerDesc *dev_layers;  // copy at the start of the arena
+    uint32_t *arrivals;       // arena: one arrival counter per (layer, sequence, kv head) for the decode launches, zero between launches
     XqStrides strides;
     std::vector<int32_t> len;  // tokens held, [layer][sequence]
     // paged cache: host mirror of the page table ([sequence][max_pages], -1 = none), pages in
@@ -150,12 +151,108 @@ struct XqDecodeArgs {
     int32_t pair_order;   // ... and the launch is a whole number of sharing groups of this many layers (0: not): deal their workgroups out side by side
     int32_t matrix;       // 0: multiply-adds on the vector ALU; 1: on the 4x4x4 fp16 matrix instruction (head_dim 128);
                           // 2: as 1 with the key phase on the 16x16x128 fp8 x fp4 instruction (2-bit keys)
+    uint32_t *arrivals;   // not null: one counter per (layer or pair of the launch, sequence, kv head), zero between
+                          // launches; the workgroup that arrives last merges the partials itself (no merge launch)
     XqPaging pg;
     int32_t seq_T[XQ_MAX_RAGGED];
 };
+#ifdef __HIPCC__
+// Log-sum-exp merge of the split partials, by one workgroup of 256 threads for NH query heads:
+// partial i of a head holds the unnormalised output o_i[D], its running maximum m_i (log2 domain)
+// and denominator l_i (D + 2 floats; a head's n_parts partials are contiguous in ws);
+//   out = sum_i o_i 2^(m_i - M) / sum_i l_i 2^(m_i - M),   M = max_i m_i.
+// Built for latency, since in a one-layer call the merge is as long as the attention itself: the
+// maxima and denominators of all partials are fetched in one round of loads, the factors
+// 2^(m_i - M) are worked out once per partial in LDS, and every thread fetches its channel of
+// eight partials (of every head) at a time before it adds them up.  The partials of an output are divided among
+// 256 / D thread groups whose sums are added in group order.  The order of every sum is fixed by
+// n_parts alone, so the result depends neither on which workgroup finished first
+// nor on who merges (the merge kernel or the last decode workgroup to arrive).
+// COHERENT: the partials were written by other workgroups of the same launch; they are read with
+// device-scope loads, which are served from beyond the reader's (per-XCD, mutually incoherent) L2.
+// head_of(v) = index of head v's partial table and output row.  lds: XQ_MERGE_LDS_FLOATS(NH) floats
+// that no thread still reads for anything else.  Every thread of the workgroup must call.
+#define XQ_MERGE_LDS_FLOATS(NH) (3 * (NH) * (XQ_MAX_SPLITS + 1) + 2 * (NH) * 256)
+template <int D, int NH, bool COHERENT, typename HeadFn>
+__device__ __forceinline__ void xq_merge_block(HeadFn head_of, const float *ws, float *out, int n_parts, float *lds, int tid) {
+    constexpr int NP = XQ_MAX_SPLITS + 1;
+    constexpr int NG = 256 / D;   // thread groups that divide the partials of an output among themselves
+    float *s_m = lds, *s_l = lds + NH * NP, *s_f = lds + 2 * NH * NP, *s_num = lds + 3 * NH * NP, *s_den = s_num + NH * 256;
+    auto ld = [](const float *x) -> float {
+        if constexpr (COHERENT) return __hip_atomic_load(x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else return *x;
+    };
+    // this thread: thread group tid / D, channel tid % D of every head; its group's partials [lo, hi)
+    const int per = (n_parts + NG - 1) / NG, pg = tid / D, ch = tid % D;
+    const int lo = pg * per, hi = min(n_parts, lo + per);
+    const float *p[NH];
+#pragma unroll
+    for (int v = 0; v < NH; ++v) p[v] = ws + head_of(v) * n_parts * (D + 2) + ch;
+    // the first eight partials of the group travel together with the maxima and denominators: one
+    // round trip to memory instead of two in the common case of at most 8 * 256 / D partials
+    float x[NH][8];
+#pragma unroll
+    for (int v = 0; v < NH; ++v)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x[v][k] = (lo + k < hi) ? ld(p[v] + (lo + k) * (D + 2)) : 0.f;
+    for (int idx = tid; idx < NH * n_parts; idx += 256) {
+        const int v = idx / n_parts, i = idx - v * n_parts;
+        const float *q = ws + (head_of(v) * n_parts + i) * (D + 2);
+        s_m[v * NP + i] = ld(q + D);
+        s_l[v * NP + i] = ld(q + D + 1);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < NH * n_parts; idx += 256) {
+        const int v = idx / n_parts, i = idx - v * n_parts;
+        float M = -INFINITY;
+        for (int j = 0; j < n_parts; ++j) M = fmaxf(M, s_m[v * NP + j]);
+        const float mi = s_m[v * NP + i];
+        s_f[v * NP + i] = (mi == -INFINITY) ? 0.f : exp2f(mi - M);
+    }
+    __syncthreads();
+    float num[NH], den[NH];
+#pragma unroll
+    for (int v = 0; v < NH; ++v) num[v] = den[v] = 0.f;
+    for (int i0 = lo; i0 < hi; i0 += 8) {
+        if (i0 > lo) {
+#pragma unroll
+            for (int v = 0; v < NH; ++v)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) x[v][k] = (i0 + k < hi) ? ld(p[v] + (i0 + k) * (D + 2)) : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < NH; ++v)
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (i0 + k < hi) {
+                    const float f = s_f[v * NP + i0 + k];
+                    num[v] = fmaf(f, x[v][k], num[v]);
+                    den[v] = fmaf(f, s_l[v * NP + i0 + k], den[v]);
+                }
+    }
+#pragma unroll
+    for (int v = 0; v < NH; ++v) {
+        s_num[v * 256 + tid] = num[v];
+        s_den[v * 256 + tid] = den[v];
+    }
+    __syncthreads();
+    for (int r = tid; r < NH * D; r += 256) {
+        const int v = r / D, c = r % D;
+        float n_ = 0.f, d_ = 0.f;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            n_ += s_num[v * 256 + g * D + c];
+            d_ += s_den[v * 256 + g * D + c];
+        }
+        out[head_of(v) * D + c] = n_ / d_;
+    }
+}
+#endif
+
 // bk, bv: bit widths of every layer in the range; pair_fused: layers come in sharing pairs;
 // n_rep in {1, 2, 4}: query heads q_head0 .. q_head0 + n_rep - 1 of every kv head.
-// Writes the split partials; xq_launch_merge turns them into the outputs.
+// Writes the split partials; xq_launch_merge turns them into the outputs (with a.arrivals set the
+// decode launch does that itself and no merge launch follows).
 hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv, int n_rep,
                             int n_layers, int pair_fused, hipStream_t s);
 hipError_t xq_launch_merge(const XqDecodeArgs &a, int D, int n_layers, hipStream_t s);

@@ -3,24 +3,12 @@
 
 namespace {
 
-// Log-sum-exp merge: partial i holds the unnormalised output o_i[D], its running max m_i
-// (log2 domain) and denominator l_i.  out = sum_i o_i 2^(m_i - M) / sum_i l_i 2^(m_i - M).
-// One thread per output channel; the order over i is fixed, so the result does not depend
-// on which workgroup finished first.
+// The merge as a launch of its own: one workgroup per query head.
 template <int D>
-__global__ __launch_bounds__(D) void xq_merge_kernel(const float *ws, float *out, int n_parts) {
+__global__ __launch_bounds__(256) void xq_merge_kernel(const float *ws, float *out, int n_parts) {
+    __shared__ float s_merge[XQ_MERGE_LDS_FLOATS(1)];
     const int64_t head = blockIdx.x;
-    const float *p = ws + head * n_parts * (D + 2);
-    float M = -INFINITY;
-    for (int i = 0; i < n_parts; ++i) M = fmaxf(M, p[i * (D + 2) + D]);
-    float num = 0.f, den = 0.f;
-    for (int i = 0; i < n_parts; ++i) {
-        float mi = p[i * (D + 2) + D];
-        float f = (mi == -INFINITY) ? 0.f : exp2f(mi - M);
-        num = fmaf(f, p[i * (D + 2) + threadIdx.x], num);
-        den = fmaf(f, p[i * (D + 2) + D + 1], den);
-    }
-    out[head * D + threadIdx.x] = num / den;
+    xq_merge_block<D, 1, false>([&](int) { return head; }, ws, out, n_parts, s_merge, threadIdx.x);
 }
 
 }  // namespace
@@ -57,8 +45,8 @@ hipError_t xq_launch_decode(const XqDecodeArgs &a, int D, int g, int bk, int bv,
 
 hipError_t xq_launch_merge(const XqDecodeArgs &a, int D, int n_layers, hipStream_t s) {
     const int64_t heads = (int64_t)n_layers * a.batch * a.n_q_heads;
-    if (D == 128) xq_merge_kernel<128><<<dim3((unsigned)heads), dim3(128), 0, s>>>(a.ws, a.out, a.n_splits + 1);
-    else xq_merge_kernel<64><<<dim3((unsigned)heads), dim3(64), 0, s>>>(a.ws, a.out, a.n_splits + 1);
+    if (D == 128) xq_merge_kernel<128><<<dim3((unsigned)heads), dim3(256), 0, s>>>(a.ws, a.out, a.n_splits + 1);
+    else xq_merge_kernel<64><<<dim3((unsigned)heads), dim3(256), 0, s>>>(a.ws, a.out, a.n_splits + 1);
     return hipGetLastError();
 }
 

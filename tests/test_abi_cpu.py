@@ -37,7 +37,7 @@ def test_exports_every_declared_symbol(xq):
 
 def test_flag_constants_match_header(xq):
     hdr = open(os.path.join(ROOT, "include", "xq.h")).read()
-    for name in ("XQ_DECODE_PAIR_FUSED", "XQ_DECODE_VECTOR_ALU", "XQ_DECODE_MATRIX_F16"):
+    for name in ("XQ_DECODE_PAIR_FUSED", "XQ_DECODE_VECTOR_ALU", "XQ_DECODE_MATRIX_F16", "XQ_DECODE_MERGE_LAUNCH", "XQ_DECODE_MERGE_IN_LAUNCH"):
         assert int(re.search(r"#define\s+%s\s+(\d+)" % name, hdr).group(1)) == getattr(xq, name)
 
 

@@ -475,10 +475,14 @@ def test_determinism_and_error_codes(lib_):
         o2 = c1.decode_attention(q, 0.1, flags=flags)
         o3 = c2.decode_attention(q, 0.1, flags=flags)
         assert torch.equal(o1, o2) and torch.equal(o1, o3)
-    # error paths of decode: bad flag, layers of different length, workspace too small
-    with pytest.raises(XqError) as e:
-        c1.decode_attention(q, 0.1, flags=8)
-    assert e.value.code == -1
+        # the merge by the last workgroup to arrive and the merge as a launch of its own: same bits
+        o4, o5 = c1.decode_attention(q, 0.1, flags=flags | 8), c1.decode_attention(q, 0.1, flags=flags | 16)
+        assert torch.equal(o1, o4) and torch.equal(o1, o5)
+    # error paths of decode: bad flags, layers of different length, workspace too small
+    for bad in (32, 8 | 16):
+        with pytest.raises(XqError) as e:
+            c1.decode_attention(q, 0.1, flags=bad)
+        assert e.value.code == -1
     c1.append_token(Kd[:2, :, :, 0].contiguous(), Vd[:2, :, :, 0].contiguous(), layer0=0)
     with pytest.raises(XqError) as e:
         c1.decode_attention(q, 0.1)
@@ -491,6 +495,38 @@ def test_determinism_and_error_codes(lib_):
     c2.workspace = small
     c1.close()
     c2.close()
+
+
+@pytest.mark.parametrize("rep,g,kq,vq,T", [(1, 32, 4, 4, 4096), (4, 64, 4, 0, 5000), (8, 32, 4, 4, 2100), (2, 32, 0, 0, 300),
+                                            (1, 32, 4, 4, 90)])
+def test_merge_by_last_arrival(lib_, rep, g, kq, vq, T):
+    """The workgroup that arrives last merges the split partials inside the decode launch: same
+    bits as the merge launch for every schedule and family, on repeated calls (the counters are back
+    at zero after each), on layer sub-ranges, with forced split counts and after appends."""
+    tl = lib_
+    w = synth.scaled(synth.workloads()[1], n_layers=4, batch=3, n_q_heads=2 * rep, n_kv_heads=2, group=g, kq=kq, vq=vq,
+                     km=0, vm=0, eta1=1 / 6, eta2=0.045, seed=300 + rep)
+    K, V = synth.kv_all(w, T + 2)
+    cache = tl.make_cache(w, max_tokens=T + 2)
+    cache.quantize_pack(K[:, :, :, :T].contiguous().cuda(), V[:, :, :, :T].contiguous().cuda())
+    q = synth.queries(w).cuda()
+    sigma = 1.0 / float(np.sqrt(w.head_dim))
+    for step in range(3):
+        for tiles in (0, 1, 3):
+            cache.set_tiles_per_split(tiles)
+            for flags in (0, 1, 2, 3, 4, 5):
+                ref = cache.decode_attention(q, sigma, flags=flags | 8)
+                for _ in range(2):
+                    assert torch.equal(cache.decode_attention(q, sigma, flags=flags | 16), ref), (step, tiles, flags)
+                assert torch.equal(cache.decode_attention(q, sigma, flags=flags), ref)      # the library's choice
+                part = cache.decode_attention(q[2:4].contiguous(), sigma, layer0=2, flags=flags | 16)
+                assert torch.equal(part, cache.decode_attention(q[2:4].contiguous(), sigma, layer0=2, flags=flags | 8))
+        if step < 2:
+            cache.append_token(K[:, :, :, T + step].contiguous().cuda(), V[:, :, :, T + step].contiguous().cuda())
+    cache.set_tiles_per_split(0)
+    st = tl.oracle_slice(w, K[:, :, :, :T + 2], V[:, :, :, :T + 2], 1, 1)
+    tl.check_attention(cache.decode_attention(q, sigma), w, tl.oracle_attention(w, st, q, 1, 1, sigma), 1, 1)
+    cache.close()
 
 
 def test_decode_refuses_code_layer_that_lags(lib_):
