@@ -280,6 +280,11 @@ int xq_cache_free_pages(const xq_cache *cache, int32_t *n_free);
  * fp32 summation order. */
 void xq_debug_set_tiles_per_split(xq_cache *cache, int32_t tiles_per_split);
 
+/* Test hook (host only, no GPU needed): the table the pack kernels use for merged pair codes
+ * (Appendix E), for bits = 1 or 2: the merged code of (e_0, e_1) sits at bit position
+ * bits * ((2^bits) * e_0 + e_1).  0 for a bad config or bit width. */
+uint32_t xq_debug_merge_table(const xq_config *cfg, int32_t bits);
+
 /* Equivalent bit-width (Appendix C): stored code bits per element averaged over layers and
  * over keys and values.  include_metadata = 0: the paper's figure (codes only).
  * include_metadata = 1: adds the fp16 scale/zero and the fp16 ring at T tokens per sequence. */

@@ -70,6 +70,8 @@ def lib():
         L.xq_code_delta_histogram.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
         L.xq_debug_set_tiles_per_split.restype = None
         L.xq_debug_set_tiles_per_split.argtypes = [vp, C.c_int32]
+        L.xq_debug_merge_table.restype = C.c_uint32
+        L.xq_debug_merge_table.argtypes = [cfgp, C.c_int32]
         L.xq_equivalent_bits.restype = C.c_double
         L.xq_equivalent_bits.argtypes = [cfgp, C.c_int32, C.c_int32]
         for name in ("xq_cache_bytes", "xq_cache_create", "xq_cache_reset", "xq_cache_len", "xq_cache_layout",

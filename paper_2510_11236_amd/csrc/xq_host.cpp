@@ -61,19 +61,28 @@ inline bool merges_next(const xq_config &c, int l, bool is_v) {
 
 // e_m for every (e_0, e_1): entry 4*e_0 + e_1 at bits [2i, 2i+1] (2-bit codes), entry 2*e_0 + e_1
 // at bit i (1-bit codes).
+// Weighted average with rounding, built from the interval table of Appendix E rather than from the
+// average itself: with delta = e_0 - e_1 > 0 the merged code is e_1 + c, where c counts the
+// interval bounds (2k - 1) / (2 delta), k = 1 .. delta, that gamma_0 has passed ((1/2); (1/4, 3/4);
+// (1/6, 1/2, 5/6)); for delta < 0 the two layers swap roles, with gamma_1 = 1 - gamma_0.  The paper
+// leaves gamma_0 exactly on a bound open; here such a value belongs to the interval above it.
+// Floor / ceil: the two ways of rounding the plain mean at gamma_0 = 1/2.
 uint32_t merge_lut(const xq_config &c, int B) {
     const int n = (1 << B) - 1;
+    const double g0 = (double)c.gamma0, g1 = 1.0 - g0;
+    auto passed = [](double g, int delta) {  // bounds of the delta row of the table that g has reached
+        int cnt = 0;
+        for (int k = 1; k <= delta; ++k)
+            if (g * (2 * delta) >= (double)(2 * k - 1)) ++cnt;
+        return cnt;
+    };
     uint32_t lut = 0;
     for (int e0 = 0; e0 <= n; ++e0)
         for (int e1 = 0; e1 <= n; ++e1) {
-            double x;
-            if (c.merge_mode == XQ_MERGE_ROUND) x = floor((double)c.gamma0 * e0 + (1.0 - (double)c.gamma0) * e1 + 0.5);
-            else if (c.merge_mode == XQ_MERGE_FLOOR) x = floor(0.5 * e0 + 0.5 * e1);
-            else if (c.merge_mode == XQ_MERGE_CEIL) x = ceil(0.5 * e0 + 0.5 * e1);
-            else x = e0;
-            int em = (int)x;
-            if (em < 0) em = 0;
-            if (em > n) em = n;
+            int em = e0;
+            if (c.merge_mode == XQ_MERGE_ROUND) em = e0 >= e1 ? e1 + passed(g0, e0 - e1) : e0 + passed(g1, e1 - e0);
+            else if (c.merge_mode == XQ_MERGE_FLOOR) em = (e0 + e1) >> 1;
+            else if (c.merge_mode == XQ_MERGE_CEIL) em = (e0 + e1 + 1) >> 1;
             lut |= (uint32_t)em << (B * ((n + 1) * e0 + e1));
         }
     return lut;
@@ -311,6 +320,7 @@ int xq_cache_create(const xq_config *cfg, void *dev_arena, size_t arena_bytes, x
         while ((1 << c->paging.shift) < cfg->page_tokens) ++c->paging.shift;
         c->page_table.assign((size_t)cfg->batch * cv.max_pages, -1);
         c->pages_used.assign(cfg->batch, 0);
+        c->want.assign(cfg->batch, 0);
         for (int p = cfg->n_pages - 1; p >= 0; --p) c->free_pages.push_back(p);  // page 0 is handed out first
     }
     c->arrivals = (uint32_t *)(c->arena + cv.arrivals);
@@ -445,6 +455,11 @@ void xq_debug_set_tiles_per_split(xq_cache *cache, int32_t tiles_per_split) {
     if (cache) cache->tiles_per_split_override = tiles_per_split;
 }
 
+uint32_t xq_debug_merge_table(const xq_config *cfg, int32_t bits) {
+    if (check_config(cfg) != XQ_OK || (bits != 1 && bits != 2)) return 0;
+    return merge_lut(*cfg, bits);
+}
+
 // With merging, the stored codes of a pair need both layers in one call.
 static bool merge_range_ok(const xq_config &c, int layer0, int n_layers) {
     if (c.merge_mode == XQ_MERGE_NONE) return true;
@@ -486,9 +501,10 @@ int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int3
     hipStream_t s = (hipStream_t)hip_stream;
     const int Tq = xq_quantized_len(T, c.group, c.residual);
     if (cache->paging.table && Tq > 0) {
-        std::vector<int32_t> want(n_seq, Tq);
-        if (pages_missing(cache, seq0, n_seq, want.data()) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
-        int rc = take_pages(cache, seq0, n_seq, want.data(), s);
+        int32_t *want = cache->want.data();
+        for (int i = 0; i < n_seq; ++i) want[i] = Tq;
+        if (pages_missing(cache, seq0, n_seq, want) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
+        int rc = take_pages(cache, seq0, n_seq, want, s);
         if (rc) return rc;
     }
     if (Tq > 0) {
@@ -566,9 +582,10 @@ int xq_prefill_attention_pack(xq_cache *cache, int32_t layer0, int32_t n_layers,
     hipStream_t s = (hipStream_t)hip_stream;
     const int Tq = pack ? xq_quantized_len(T, c.group, c.residual) : 0;
     if (pack && cache->paging.table && Tq > 0) {
-        std::vector<int32_t> want(c.batch, Tq);
-        if (pages_missing(cache, 0, c.batch, want.data()) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
-        int rc = take_pages(cache, 0, c.batch, want.data(), s);
+        int32_t *want = cache->want.data();
+        for (int i = 0; i < c.batch; ++i) want[i] = Tq;
+        if (pages_missing(cache, 0, c.batch, want) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
+        int rc = take_pages(cache, 0, c.batch, want, s);
         if (rc) return rc;
     }
     XqPrefillArgs a;
@@ -646,14 +663,15 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
                 return XQ_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
     if (cache->paging.table) {  // pages for the groups that this call's ring flushes will write
-        std::vector<int32_t> want(c.batch, 0);
+        int32_t *want = cache->want.data();
+        for (int i = 0; i < c.batch; ++i) want[i] = 0;
         for (int l = layer0; l < layer0 + n_layers; ++l)
             for (int i = 0; i < c.batch; ++i) {
                 const int t = len_row(cache, l)[i], tq = xq_quantized_len(t, c.group, c.residual);
                 want[i] = std::max(want[i], t - tq == c.residual ? tq + c.group : tq);
             }
-        if (pages_missing(cache, 0, c.batch, want.data()) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
-        int rc = take_pages(cache, 0, c.batch, want.data(), s);
+        if (pages_missing(cache, 0, c.batch, want) > (int64_t)cache->free_pages.size()) return XQ_ERR_CAPACITY;
+        int rc = take_pages(cache, 0, c.batch, want, s);
         if (rc) return rc;
     }
     const int64_t D = c.head_dim;

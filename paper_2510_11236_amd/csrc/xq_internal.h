@@ -67,6 +67,7 @@ struct xq_cache {
     // use per sequence, free pages (a stack), device table inside the arena
     XqPaging paging;           // table == nullptr for a contiguous cache
     std::vector<int32_t> page_table, pages_used, free_pages;
+    std::vector<int32_t> want;  // packed tokens each sequence is about to hold (sized once, at create: no allocation per call)
     int32_t tiles_per_split_override;  // 0 = automatic
 };
 

@@ -1,6 +1,6 @@
-// Wave-level quantize + bit-pack of one token group (head_dim 128): device functions shared by the
-// pack kernels (xq_pack.hip) and by the prompt-attention kernel that packs the K/V tiles it already
-// holds (xq_prefill.hip).  Arithmetic contract: include/xq.h.
+// Wave-level quantize + bit-pack of token groups: device functions shared by the pack kernel
+// (xq_pack.hip) and by the prompt-attention kernel that packs the K/V tiles it already holds
+// (xq_prefill.hip).  Arithmetic contract: include/xq.h.
 #pragma once
 #include "xq_internal.h"
 
@@ -31,8 +31,10 @@ __device__ __forceinline__ float group_params(float mn, float mx, int n, float c
 }
 
 // ------------------------------------------------------------------------------------------
-// Wave-per-tile pack kernel for D = 128 (the production shape).  One wave quantizes the keys
-// or the values of one token group: lane = channel pair, the g token rows stay in registers.
+// One wave quantizes the keys or the values of one token group (head_dim 128) or of two
+// neighbouring ones (head_dim 64: one group per half of the wave): lane = channel pair of its
+// group, the g token rows stay in registers.  Everything that crosses lanes stays inside 32 lanes
+// or fewer, so the two halves never mix; slice, dst_tok (and the row registers) are per lane.
 //
 // Codes without a division per element.  The contract is c = rint(RN((x - mn) / s)) with ties
 // to even.  RN(d / s) is monotone in d, so c = [d >= D1] + [d >= D2] + [d >= D3] where Dk is
@@ -144,11 +146,13 @@ __device__ __forceinline__ uint32_t dpp_or(uint32_t x) {
     return x | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
 }
 
-// MG: the stored codes are merged with the next layer's own codes, whose rows are rows2.
-template <int G, int B, bool MG>
+// MG: the stored codes are merged with the next layer's own codes, whose rows are rows2; that
+// layer's metadata (descriptor d2) is written here as well, so that its rows are read once.
+template <int G, int B, bool MG, int D = 128>
 __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
-                                               const uint32_t (&rows2)[MG ? G : 1], int lane, int64_t slice, int dst_tok) {
-    constexpr int D = 128;
+                                               const uint32_t (&rows2)[MG ? G : 1], int lane, int64_t slice, int dst_tok,
+                                               const XqLayerDesc *d2 = nullptr) {
+    lane %= D / 2;  // channel pair inside the lane's group
     // ---- per-channel min / max down the g tokens (two channels per lane)
     uint32_t pa = 0x7c007c00u, pb = 0x7c007c00u;  // (+inf, +inf)
 #pragma unroll
@@ -167,7 +171,7 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     mab.y = mb;
     __builtin_nontemporal_store(mab, (u32x2 *)mp);  // streamed out once: keep it out of the way of the reads
     if (!d.k_store) return;
-    GroupQ q2a = qa, q2b = qb;  // the next layer's own groups (its metadata is written by its own wave)
+    GroupQ q2a = qa, q2b = qb;  // the next layer's own groups
     if constexpr (MG) {
         uint32_t pa2 = 0x7c007c00u, pb2 = 0x7c007c00u;
 #pragma unroll
@@ -175,15 +179,20 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
             pa2 = minmax_lo(pa2, rows2[t]);
             pb2 = minmax_hi(pb2, rows2[t]);
         }
-        uint32_t unused;
-        q2a = group_quant<B>(pair_min(pa2), pair_max(pa2), c1, c2, &unused);
-        q2b = group_quant<B>(pair_min(pb2), pair_max(pb2), c1, c2, &unused);
+        uint32_t m2a, m2b;
+        q2a = group_quant<B>(pair_min(pa2), pair_max(pa2), c1, c2, &m2a);
+        q2b = group_quant<B>(pair_min(pb2), pair_max(pb2), c1, c2, &m2b);
+        u32x2 m2;
+        m2.x = m2a;
+        m2.y = m2b;
+        uint32_t *mp2 = (uint32_t *)(a.arena + d2->k_meta + slice * a.st.k_meta) + (int64_t)(dst_tok / G) * D + 2 * lane;
+        __builtin_nontemporal_store(m2, (u32x2 *)mp2);
     }
     const uint32_t lut = B == 2 ? a.lut2 : a.lut1;
     // ---- codes: a word holds 32/B channels of one token = LW lanes x (2 channels x B bits)
     constexpr int LW = 16 / B;             // lanes per word
     constexpr int W = D * B / 32;          // words per token row
-    constexpr int CW = 4;
+    constexpr int CW = W < 4 ? W : 4;      // words of a row that lie together (a 16-byte chunk when the row has them)
     uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + slice * (B == 2 ? a.st.k_codes2 : a.st.k_codes1));
     const int wsel = lane / LW, lsel = lane % LW;
     // batches of LW rows: the OR trees of a batch run side by side, so that no instruction
@@ -222,11 +231,16 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     }
 }
 
-template <int G, int B, bool MG>
+template <int G, int B, bool MG, int D = 128>
 __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
                                                  const uint32_t (&rows2)[MG ? G : 1], int lane, int64_t slice, int dst_tok,
-                                                 float4 *s_par, float4 *s_par2) {
-    constexpr int D = 128, NJ = D / G, LPG = G / 2;  // lanes per channel group
+                                                 float4 *s_par, float4 *s_par2, const XqLayerDesc *d2 = nullptr) {
+    constexpr int NJ = D / G, LPG = G / 2;  // lanes per channel group
+    if constexpr (D == 64) {                // the half wave's own group parameters
+        s_par += (lane / 32) * G * NJ;
+        s_par2 += MG ? (lane / 32) * G * NJ : 0;
+        lane %= 32;
+    }
     const int j = lane / LPG, i = lane % LPG;
     const float c1 = B == 2 ? a.c1_2 : a.c1_1, c2 = B == 2 ? a.c2_2 : a.c2_1;
     uint32_t *mp = (uint32_t *)(a.arena + d.v_meta + slice * a.st.v_meta) + (int64_t)dst_tok * NJ;
@@ -248,7 +262,7 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
         const int t = c * LPG + i;
         __builtin_nontemporal_store(meta, &mp[t * NJ + j]);
         s_par[t * NJ + j] = make_float4(q.nmn, q.D1, q.D2, q.D3);
-        if constexpr (MG) {  // the next layer's own group of the same token
+        if constexpr (MG) {  // the next layer's own group of the same token, and its metadata
             uint32_t mine2 = 0;
 #pragma unroll
             for (int k = 0; k < LPG; ++k) {
@@ -258,8 +272,10 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
                 for (int o = 1; o < LPG; o <<= 1) p = pk_min(p, (uint32_t)__shfl_xor((int)p, o, 64));
                 mine2 = (i == k) ? p : mine2;
             }
-            uint32_t unused;
-            const GroupQ q2 = group_quant<B>(pair_min(mine2), pair_max(mine2), c1, c2, &unused);
+            uint32_t meta2;
+            const GroupQ q2 = group_quant<B>(pair_min(mine2), pair_max(mine2), c1, c2, &meta2);
+            uint32_t *mp2 = (uint32_t *)(a.arena + d2->v_meta + slice * a.st.v_meta) + (int64_t)dst_tok * NJ;
+            __builtin_nontemporal_store(meta2, &mp2[t * NJ + j]);
             s_par2[t * NJ + j] = make_float4(q2.nmn, q2.D1, q2.D2, q2.D3);
         }
     }
@@ -268,9 +284,33 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // ---- codes: this lane's two channels over TPW tokens fill one word, highest token first
-    constexpr int TPW = 16 / B;   // tokens per word
-    constexpr int WS = 2 * B;     // words per 32-token block
+    // the code of element (token t, low / high channel of the lane), pushed into w
+    auto push = [&](uint32_t w, int t, bool hi) {
+        const float4 f = s_par[t * NJ + j];
+        GroupQ q;
+        q.nmn = f.x;
+        q.D1 = f.y;
+        q.D2 = f.z;
+        q.D3 = f.w;
+        const float dd = hi ? sub_hi(rows[t], q.nmn) : sub_lo(rows[t], q.nmn);
+        if constexpr (MG) {
+            const float4 f2 = s_par2[t * NJ + j];
+            GroupQ q2;
+            q2.nmn = f2.x;
+            q2.D1 = f2.y;
+            q2.D2 = f2.z;
+            q2.D3 = f2.w;
+            return (w << B) | merged_code<B>(dd, q, hi ? sub_hi(rows2[t], q2.nmn) : sub_lo(rows2[t], q2.nmn), q2, lut);
+        } else {
+            return push_code<B>(w, dd, q);
+        }
+    };
+    // ---- codes.  head_dim 128: this lane's two channels over TPW tokens fill one word, highest
+    // token first.  head_dim 64: a slot of the layout is one channel, so each of the lane's two
+    // channels fills words of its own with 32 / B tokens each; the two slots are neighbours, the
+    // lane still stores 2 B words per 32-token block in one piece.
+    constexpr int TPW = (D == 128 ? 16 : 32) / B;   // tokens per word
+    constexpr int WS = 2 * B;                       // words per lane and 32-token block
     uint32_t *cp = (uint32_t *)(a.arena + d.v_codes + slice * (B == 2 ? a.st.v_codes2 : a.st.v_codes1));
 #pragma unroll
     for (int blk = 0; blk < G / 32; ++blk) {
@@ -280,30 +320,18 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
             uint32_t w = 0;
 #pragma unroll
             for (int k = TPW - 1; k >= 0; --k) {
-                const int t = blk * 32 + m * TPW + k;
-                const float4 f = s_par[t * NJ + j];
-                GroupQ q;
-                q.nmn = f.x;
-                q.D1 = f.y;
-                q.D2 = f.z;
-                q.D3 = f.w;
-                if constexpr (MG) {
-                    const float4 f2 = s_par2[t * NJ + j];
-                    GroupQ q2;
-                    q2.nmn = f2.x;
-                    q2.D1 = f2.y;
-                    q2.D2 = f2.z;
-                    q2.D3 = f2.w;
-                    w = (w << B) | merged_code<B>(sub_hi(rows[t], q.nmn), q, sub_hi(rows2[t], q2.nmn), q2, lut);
-                    w = (w << B) | merged_code<B>(sub_lo(rows[t], q.nmn), q, sub_lo(rows2[t], q2.nmn), q2, lut);
+                if constexpr (D == 128) {
+                    const int t = blk * 32 + m * TPW + k;
+                    w = push(w, t, true);
+                    w = push(w, t, false);
                 } else {
-                    w = push_code<B>(w, sub_hi(rows[t], q.nmn), q);
-                    w = push_code<B>(w, sub_lo(rows[t], q.nmn), q);
+                    const int t = blk * 32 + (m % B) * TPW + k;   // words 0 .. B - 1: low channel, then the high one
+                    w = push(w, t, m >= B);
                 }
             }
             words[m] = w;
         }
-        uint32_t *wp = cp + (int64_t)(dst_tok / 32 + blk) * 64 * WS + lane * WS;
+        uint32_t *wp = cp + (int64_t)(dst_tok / 32 + blk) * (D / 2) * WS + lane * WS;
         typedef uint32_t u32xw __attribute__((ext_vector_type(WS)));
         u32xw wv;
 #pragma unroll

@@ -120,3 +120,38 @@ def test_paged_config_checks(xq):
     # half the pool: half the packed bytes (the fp16 rings are not paged)
     a2, _ = xq.cache_bytes(_cfg(xq, max_tokens=4096 + 128, page_tokens=128, n_pages=2 * 32))
     assert a2 < 0.65 * a0
+
+
+def _merge_table(xq, bits, mode, gamma0):
+    lut = xq.lib().xq_debug_merge_table(C.byref(_cfg(xq, merge_mode=mode, gamma0=gamma0)), bits)
+    n = 1 << bits
+    return [[(lut >> (bits * (n * e0 + e1))) & (n - 1) for e1 in range(n)] for e0 in range(n)]
+
+
+def test_merge_table_follows_appendix_e_intervals(xq):
+    """The pack kernels' table of merged codes against the interval table of Appendix E
+    (tests/golden/gamma_intervals.txt: e_m = e_1 + c for gamma_0 inside the listed interval, and the
+    mirrored case with gamma_1), against the oracle's weighted average over a sweep of gamma_0, and
+    floor / ceil of the plain mean."""
+    from fractions import Fraction
+    import numpy as np
+    from oracle import xq_oracle as orc
+    for delta, c, lo, hi in _gold("gamma_intervals.txt"):
+        delta, c, lo, hi = int(delta), int(c), Fraction(lo), Fraction(hi)
+        for frac in (Fraction(1, 64), Fraction(1, 2), Fraction(63, 64)):
+            g0 = float(lo + (hi - lo) * frac)
+            t, tm = _merge_table(xq, 2, 1, g0), _merge_table(xq, 2, 1, 1.0 - g0)
+            for e1 in range(0, 4 - delta):
+                assert t[e1 + delta][e1] == e1 + c, (delta, c, g0)
+                assert tm[e1][e1 + delta] == e1 + c, (delta, c, g0)      # e_1 > e_0: gamma_1 plays gamma_0's part
+    e = np.arange(4, dtype=np.uint8)
+    e0, e1 = np.repeat(e, 4), np.tile(e, 4)
+    for g0 in list(np.linspace(0.0, 1.0, 41)) + [0.166, 0.167, 0.8333, 0.8334, 0.2499, 0.7501]:
+        g0 = float(np.float32(g0))
+        ref = orc.merge_codes(e0, e1, 2, 1, g0).reshape(4, 4)
+        assert np.array_equal(np.array(_merge_table(xq, 2, 1, g0)), ref), g0
+        ref1 = orc.merge_codes(np.array([0, 0, 1, 1], np.uint8), np.array([0, 1, 0, 1], np.uint8), 1, 1, g0).reshape(2, 2)
+        assert np.array_equal(np.array(_merge_table(xq, 1, 1, g0)), ref1), g0
+    for mode, f in ((2, lambda a, b: (a + b) // 2), (3, lambda a, b: (a + b + 1) // 2)):
+        assert _merge_table(xq, 2, mode, 0.5) == [[f(a, b) for b in range(4)] for a in range(4)]
+    assert xq.lib().xq_debug_merge_table(C.byref(_cfg(xq, merge_mode=1, gamma0=0.5)), 3) == 0
