@@ -231,6 +231,43 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     }
 }
 
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_from(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+
+// (min, -max) of token `first + i` over the LPG lanes of lane i's channel group, from the lanes' own
+// (min, -max) of their two channels for tokens first .. first + LPG - 1.  Instead of a full
+// exchange per token (LPG log2 LPG shuffles), the lanes halve the set of tokens they are responsible
+// for at every step and hand the other half to their partner: LPG - 1 exchanges in all, all but the
+// 32-lane step by DPP.  Partners: lane ^ 16, mirror inside 16, mirror inside 8, lane ^ 2, lane ^ 1;
+// a lane keeps the tokens whose index has its own bit at that step, so it ends with token i.
+template <int G, int LPG>
+__device__ __forceinline__ uint32_t token_minmax(const uint32_t (&rows)[G], int first, int i) {
+    uint32_t q[16];
+    if constexpr (LPG == 32) {
+        const bool up = (i & 16) != 0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint32_t lo = minmax_hi(minmax_lo(0x7c007c00u, rows[first + k]), rows[first + k]);
+            const uint32_t hi = minmax_hi(minmax_lo(0x7c007c00u, rows[first + 16 + k]), rows[first + 16 + k]);
+            q[k] = pk_min(up ? hi : lo, (uint32_t)__shfl_xor((int)(up ? lo : hi), 16, 64));
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) q[k] = minmax_hi(minmax_lo(0x7c007c00u, rows[first + k]), rows[first + k]);
+    }
+    const bool b3 = (i & 8) != 0, b2 = (i & 4) != 0, b1 = (i & 2) != 0, b0 = (i & 1) != 0;
+    uint32_t y[8], z[4], w[2];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) y[k] = pk_min(b3 ? q[8 + k] : q[k], dpp_from<0x140>(b3 ? q[k] : q[8 + k]));
+#pragma unroll
+    for (int k = 0; k < 4; ++k) z[k] = pk_min(b2 ? y[4 + k] : y[k], dpp_from<0x141>(b2 ? y[k] : y[4 + k]));
+#pragma unroll
+    for (int k = 0; k < 2; ++k) w[k] = pk_min(b1 ? z[2 + k] : z[k], dpp_from<0x4E>(b1 ? z[k] : z[2 + k]));
+    return pk_min(b0 ? w[1] : w[0], dpp_from<0xB1>(b0 ? w[0] : w[1]));
+}
+
 template <int G, int B, bool MG, int D = 128>
 __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLayerDesc &d, const uint32_t (&rows)[G],
                                                  const uint32_t (&rows2)[MG ? G : 1], int lane, int64_t slice, int dst_tok,
@@ -244,34 +281,18 @@ __device__ __forceinline__ void pack_values_wave(const XqPackArgs &a, const XqLa
     const int j = lane / LPG, i = lane % LPG;
     const float c1 = B == 2 ? a.c1_2 : a.c1_1, c2 = B == 2 ? a.c2_2 : a.c2_1;
     uint32_t *mp = (uint32_t *)(a.arena + d.v_meta + slice * a.st.v_meta) + (int64_t)dst_tok * NJ;
-    // ---- per-token min / max along the g channels of a group: reduce over the LPG lanes, then
-    // lane i of the group keeps token (chunk * LPG + i), so each lane owns one group's parameters
+    // ---- per-token min / max along the g channels of a group: lane i of the group ends up with
+    // token (chunk * LPG + i), so each lane owns one group's parameters
 #pragma unroll
     for (int c = 0; c < G / LPG; ++c) {
-        uint32_t mine = 0;
-#pragma unroll
-        for (int k = 0; k < LPG; ++k) {
-            const int t = c * LPG + k;
-            uint32_t p = minmax_hi(minmax_lo(0x7c007c00u, rows[t]), rows[t]);
-#pragma unroll
-            for (int o = 1; o < LPG; o <<= 1) p = pk_min(p, (uint32_t)__shfl_xor((int)p, o, 64));
-            mine = (i == k) ? p : mine;
-        }
+        const uint32_t mine = token_minmax<G, LPG>(rows, c * LPG, i);
         uint32_t meta;
         const GroupQ q = group_quant<B>(pair_min(mine), pair_max(mine), c1, c2, &meta);
         const int t = c * LPG + i;
         __builtin_nontemporal_store(meta, &mp[t * NJ + j]);
         s_par[t * NJ + j] = make_float4(q.nmn, q.D1, q.D2, q.D3);
         if constexpr (MG) {  // the next layer's own group of the same token, and its metadata
-            uint32_t mine2 = 0;
-#pragma unroll
-            for (int k = 0; k < LPG; ++k) {
-                const int t2 = c * LPG + k;
-                uint32_t p = minmax_hi(minmax_lo(0x7c007c00u, rows2[t2]), rows2[t2]);
-#pragma unroll
-                for (int o = 1; o < LPG; o <<= 1) p = pk_min(p, (uint32_t)__shfl_xor((int)p, o, 64));
-                mine2 = (i == k) ? p : mine2;
-            }
+            const uint32_t mine2 = token_minmax<G, LPG>(rows2, c * LPG, i);
             uint32_t meta2;
             const GroupQ q2 = group_quant<B>(pair_min(mine2), pair_max(mine2), c1, c2, &meta2);
             uint32_t *mp2 = (uint32_t *)(a.arena + d2->v_meta + slice * a.st.v_meta) + (int64_t)dst_tok * NJ;
