@@ -247,7 +247,12 @@ def main():
     # --schedule auto times both schedules (untimed probes) and takes the faster; an explicit
     # schedule runs no probes, so that a profile of the run holds only warmup + timed launches
     alu = FAMILY_FLAGS[args.family]
-    can_fuse = any(l % 2 == 1 and (l >= w.km or l >= w.vm) for l in range(w.n_layers))
+    # a pair shares a workgroup only when some odd layer shares both code sets and the kernel's weight
+    # tables hold two layers of every query-head part (4, 2, 1) of a kv head: 2 * part * 128 / g <= 16
+    rep = w.n_q_heads // w.n_kv_heads
+    parts = [4] * (rep // 4) + [2] * (rep % 4 // 2) + [1] * (rep % 2) if w.head_dim == 128 else [1]
+    can_fuse = (any(l % 2 == 1 and l >= w.km and l >= w.vm for l in range(w.n_layers)) and
+                all(2 * p * (128 // w.group) <= 16 for p in parts))
     probe = {}
     if args.schedule == "auto":
         probe["sequential"] = time_decode(alu, 20)
