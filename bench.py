@@ -54,10 +54,8 @@ def algorithmic_bytes(w, T, fused):
         v_shared = not (l < w.vm or l % 2 == 0)
         k_codes = Tq * D * bk // 8
         v_codes = Tq * D * bv // 8
-        if fused and k_shared:
-            k_codes = 0
-        if fused and v_shared:
-            v_codes = 0
+        if fused and k_shared and v_shared:   # the library fuses a pair only when it shares both code sets
+            k_codes = v_codes = 0
         meta = Tq * D * 4 // g * 2
         ring = r * D * 2 * 2
         total += nbh * (k_codes + v_codes + meta + ring)
