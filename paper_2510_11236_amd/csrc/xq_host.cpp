@@ -217,7 +217,7 @@ size_t workspace_floats(const xq_config &c, int n_layers, int n_splits) {
 // kernel variant (n_rep query heads per kv head in the pass; a fused pair doubles the heads).
 int decode_wgs_per_cu(int matrix, int n_rep, bool fused, int g, int bk, int bv) {
     const int nv = n_rep * (fused ? 2 : 1);
-    if (matrix == 2 && xq_decode_has_kx(128, g, bk, n_rep, fused)) return nv > 4 || g == 32 ? 2 : 3;
+    if (matrix == 2 && xq_decode_has_kx(128, g, bk, n_rep, fused)) return 2;
     if (matrix) {
         if (nv <= 2 || (n_rep == 4 && !fused && g == 64 && bk + bv < 4)) return 4;
         return nv <= 4 ? 3 : 2;

@@ -142,8 +142,37 @@ __device__ __forceinline__ uint32_t merged_code(float d0, const GroupQ &q0, floa
 }
 
 template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_or(uint32_t x) {
-    return x | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+__device__ __forceinline__ uint32_t dpp_from(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+
+// One step of a transpose between lanes and bit fields: lanes H apart exchange the fields they hold
+// for each other.  w holds fields in blocks of S bits; a lane whose index has bit H clear keeps its
+// even blocks and receives the partner's even blocks into its odd ones, a lane with the bit set the
+// other way round.  p = the partner's w.
+template <int S>
+__device__ __forceinline__ uint32_t exchange_blocks(uint32_t w, uint32_t p, bool upper) {
+    constexpr uint32_t EVEN = S == 16 ? 0x0000ffffu : S == 8 ? 0x00ff00ffu : S == 4 ? 0x0f0f0f0fu : 0x33333333u;
+    const uint32_t keep = upper ? ~EVEN : EVEN;
+    const uint32_t moved = __builtin_amdgcn_alignbit(p, p, upper ? S : 32 - S);   // rotate right: down by S, or up by S
+    return (w & keep) | (moved & ~keep);
+}
+
+// LW lanes each hold a word of LW fields of 32 / LW bits, field k of lane l being element (l, k);
+// afterwards field l of lane k is that element: lane k holds what the LW lanes had at position k.
+// Partners by DPP: lane ^ 8 = rotate the 16-lane row by 8; lane ^ 4 = shift the row up by 4 for the
+// lanes of banks 0 and 2, down by 4 for banks 1 and 3; lane ^ 2 and lane ^ 1 = quad permutations.
+template <int LW>
+__device__ __forceinline__ uint32_t transpose_lanes_fields(uint32_t w, int lsel) {
+    constexpr int E = 32 / LW;
+    if constexpr (LW == 16) w = exchange_blocks<8 * E>(w, dpp_from<0x128>(w), (lsel & 8) != 0);
+    {
+        uint32_t p = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x104, 0xf, 0x5, false);   // lane + 4
+        p = (uint32_t)__builtin_amdgcn_update_dpp((int)p, (int)w, 0x114, 0xf, 0xa, false);          // lane - 4
+        w = exchange_blocks<4 * E>(w, p, (lsel & 4) != 0);
+    }
+    w = exchange_blocks<2 * E>(w, dpp_from<0x4E>(w), (lsel & 2) != 0);
+    return exchange_blocks<E>(w, dpp_from<0xB1>(w), (lsel & 1) != 0);
 }
 
 // MG: the stored codes are merged with the next layer's own codes, whose rows are rows2; that
@@ -195,45 +224,28 @@ __device__ __forceinline__ void pack_keys_wave(const XqPackArgs &a, const XqLaye
     constexpr int CW = W < 4 ? W : 4;      // words of a row that lie together (a 16-byte chunk when the row has them)
     uint32_t *cp = (uint32_t *)(a.arena + d.k_codes + slice * (B == 2 ? a.st.k_codes2 : a.st.k_codes1));
     const int wsel = lane / LW, lsel = lane % LW;
-    // batches of LW rows: the OR trees of a batch run side by side, so that no instruction
-    // waits on the DPP read-after-write hazard of its own row
+    // Each lane first fills a word with its own two channels of LW tokens (the compare chains shift
+    // the codes in, highest token first, at no extra cost), then the LW lanes of a word transpose
+    // lanes against fields: lane lsel ends up with the two-channel fields of all LW lanes for token
+    // t0 + lsel, in lane (= channel) order -- the stored word.
 #pragma unroll
     for (int t0 = 0; t0 < G; t0 += LW) {
-        uint32_t x[LW];
+        uint32_t w = 0;
 #pragma unroll
-        for (int k = 0; k < LW; ++k) {
-            uint32_t nib;
+        for (int k = LW - 1; k >= 0; --k) {
             if constexpr (MG) {
-                nib = merged_code<B>(sub_hi(rows[t0 + k], qb.nmn), qb, sub_hi(rows2[t0 + k], q2b.nmn), q2b, lut) << B;
-                nib |= merged_code<B>(sub_lo(rows[t0 + k], qa.nmn), qa, sub_lo(rows2[t0 + k], q2a.nmn), q2a, lut);
+                w = (w << B) | merged_code<B>(sub_hi(rows[t0 + k], qb.nmn), qb, sub_hi(rows2[t0 + k], q2b.nmn), q2b, lut);
+                w = (w << B) | merged_code<B>(sub_lo(rows[t0 + k], qa.nmn), qa, sub_lo(rows2[t0 + k], q2a.nmn), q2a, lut);
             } else {
-                nib = push_code<B>(0u, sub_hi(rows[t0 + k], qb.nmn), qb);
-                nib = push_code<B>(nib, sub_lo(rows[t0 + k], qa.nmn), qa);
+                w = push_code<B>(w, sub_hi(rows[t0 + k], qb.nmn), qb);
+                w = push_code<B>(w, sub_lo(rows[t0 + k], qa.nmn), qa);
             }
-            x[k] = nib << (2 * B * lsel);
         }
-#pragma unroll
-        for (int k = 0; k < LW; ++k) x[k] = dpp_or<0xB1>(x[k]);    // lanes ^ 1
-#pragma unroll
-        for (int k = 0; k < LW; ++k) x[k] = dpp_or<0x4E>(x[k]);    // lanes ^ 2
-#pragma unroll
-        for (int k = 0; k < LW; ++k) x[k] = dpp_or<0x141>(x[k]);   // mirror inside each 8 lanes
-        if (LW == 16) {
-#pragma unroll
-            for (int k = 0; k < LW; ++k) x[k] = dpp_or<0x140>(x[k]);  // mirror inside the 16-lane row
-        }
-        uint32_t keep = x[0];
-#pragma unroll
-        for (int k = 1; k < LW; ++k) keep = (lsel == k) ? x[k] : keep;
+        const uint32_t keep = transpose_lanes_fields<LW>(w, lsel);
         // lane (wsel, lsel) holds word wsel of token t0 + lsel
         const int tok = dst_tok + t0 + lsel;
         __builtin_nontemporal_store(keep, &cp[(int64_t)(tok / 32) * 32 * W + (wsel / CW) * 32 * CW + (tok % 32) * CW + wsel % CW]);
     }
-}
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_from(uint32_t x) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
 }
 
 // (min, -max) of token `first + i` over the LPG lanes of lane i's channel group, from the lanes' own
