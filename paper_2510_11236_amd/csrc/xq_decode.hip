@@ -1091,15 +1091,29 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 acr[v][c] = 0.f;
             }
         const int r = seqT - seqTq;
-        for (int i = wave * 4 + row; i < r; i += 16) {
-            const int slot = (seqTq + i) % a.R;
+        // the rows of the row's next token are fetched while the current one is worked on: with one
+        // workgroup per ring the walk is a chain of memory latencies otherwise, and in a call for one
+        // layer of a short cache the ring workgroup is the last to finish
+        uint32_t kn[NLAY][CR / 2], vn[NLAY][CR / 2];
+        auto ring_load = [&](int i) {
+            const int slot = (seqTq + min(i, r - 1)) % a.R;   // (past the end: the last token again, not used)
 #pragma unroll
             for (int y = 0; y < NLAY; ++y) {
-                const uint32_t *kp = (const uint32_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2;
-                const uint32_t *vp = (const uint32_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2;
+                VecLoad<CR / 2>::ld((const uint32_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2, kn[y]);
+                VecLoad<CR / 2>::ld((const uint32_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2, vn[y]);
+            }
+        };
+        if (r > 0) ring_load(wave * 4 + row);
+        for (int i = wave * 4 + row; i < r; i += 16) {
+#pragma unroll
+            for (int y = 0; y < NLAY; ++y) {
                 uint32_t kw[CR / 2], vw[CR / 2];
-                VecLoad<CR / 2>::ld(kp, kw);
-                VecLoad<CR / 2>::ld(vp, vw);
+#pragma unroll
+                for (int c = 0; c < CR / 2; ++c) {
+                    kw[c] = kn[y][c];
+                    vw[c] = vn[y][c];
+                }
+                if (y == NLAY - 1) ring_load(i + 16);
                 float kf[CR], vf[CR];
 #pragma unroll
                 for (int c = 0; c < CR; ++c) {
