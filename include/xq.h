@@ -21,7 +21,8 @@
  *     Kernels are enqueued on it and the call returns without waiting.  Length
  *     bookkeeping in the host handle advances at call time, so calls on one
  *     handle must be issued in program order from one thread at a time.
- *     Apart from xq_cache_create (one synchronous copy of the layer table into the arena)
+ *     Apart from xq_cache_create (one synchronous copy of the layer table into the arena and a
+ *     clear of the arrival counters that the decode launches keep there)
  *     the calls only launch kernels: no allocation, no memset, no synchronisation.  A call may
  *     therefore be recorded by HIP stream capture; a replay repeats the recorded lengths.
  *   - fp16 = IEEE binary16.  Inputs must be finite.
