@@ -61,6 +61,7 @@ def test_paged_equals_contiguous(tl, D, g, P, rep, T0, n_app):
             plain.set_tiles_per_split(tps)
             paged.set_tiles_per_split(tps)
             assert torch.equal(plain.decode_attention(q, sigma, flags=flags), paged.decode_attention(q, sigma, flags=flags))
+            assert torch.equal(paged.decode_attention(q, sigma, flags=flags | 16), paged.decode_attention(q, sigma, flags=flags | 8))
     out = paged.decode_attention(q, sigma, flags=1)
     for bi in range(w.batch):
         for h in range(w.n_kv_heads):

@@ -393,6 +393,10 @@ def test_ragged_batch(lib_, rep, g, vq):
 
     def check(step):
         outs = [cache.decode_attention(q, sigma), cache.decode_attention(q, sigma, flags=1)]
+        # shorter sequences leave workgroups with no tile: they must still be counted in when the
+        # last arrival merges, and the merge launch must see their empty partials (same bits)
+        for f in (0, 1, 2, 4):
+            assert torch.equal(cache.decode_attention(q, sigma, flags=f | 16), cache.decode_attention(q, sigma, flags=f | 8)), f
         for bi, T in enumerate(lens):
             T = T + step
             assert cache.length(0, bi)[0] == T
