@@ -34,7 +34,7 @@ constexpr int PF_KROW = 132;   // halves per K (and row-major V) row in LDS: 128
 constexpr int PF_VROW = 68;    // halves per row of the transposed V tile: 64 tokens + 4
 
 template <int G, bool PACK>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))  // 256 registers: two workgroups per CU
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))  // at most 168 registers: three workgroups per CU
 void xq_prefill_kernel(XqPrefillArgs a) {
     constexpr int D = 128;
     __shared__ __attribute__((aligned(16))) _Float16 s_k[PF_BN * PF_KROW];
