@@ -174,6 +174,7 @@ int xq_quantize_pack_seq(xq_cache *cache, int32_t layer0, int32_t n_layers, int3
  * so that K and V come from HBM once instead of twice.
  * q_f16: device fp16 [n_layers][batch][n_q_heads][T][128], contiguous; out_f32: device fp32, same
  * shape; k_f16, v_f16, strides, T: as for xq_quantize_pack (all sequences, empty layers).
+ * sm_scale must be positive and finite.
  * flags: 0, or XQ_PREFILL_NO_PACK for the attention alone (the cache is not touched).
  * XQ_ERR_UNSUPPORTED for head_dim 64 and, when packing, for caches with merged pair codes. */
 #define XQ_PREFILL_NO_PACK 1

@@ -564,6 +564,7 @@ int xq_prefill_attention_pack(xq_cache *cache, int32_t layer0, int32_t n_layers,
     if (!range_ok(cache, layer0, n_layers) || !q_f16 || !k_f16 || !v_f16 || !out_f32 || !strides || T < 1)
         return XQ_ERR_INVALID_ARG;
     if (flags & ~XQ_PREFILL_NO_PACK) return XQ_ERR_INVALID_ARG;
+    if (!(sm_scale > 0.0f) || !(sm_scale < INFINITY)) return XQ_ERR_INVALID_ARG;  // the kernel takes the running maximum before scaling
     const xq_config &c = cache->cfg;
     if (c.head_dim != 128) return XQ_ERR_UNSUPPORTED;
     const bool pack = !(flags & XQ_PREFILL_NO_PACK);

@@ -13,34 +13,39 @@
 //
 // Attention: one workgroup = 128 queries of one query head; wave w owns queries 32 w .. 32 w + 31.
 // Key/value tiles of 64 tokens go through LDS: K row-major, V transposed.  Both products run on
-// v_mfma_f32_32x32x8_f16 with the LDS tile as A and the wave's registers as B:
+// v_mfma_f32_32x32x16_f16 with the LDS tile as A and the wave's registers as B:
 //   S^T = K Q^T   (rows = tokens, columns = the wave's queries; B = the lane's query row, loaded once)
 //   O^T = V^T P^T (rows = channels, columns = queries; B = P^T straight from S^T's result registers:
-//                  a lane of the 32x32 result holds, for its column, rows 8 i + 4 (lane / 32) + j,
-//                  which is exactly the four-k-per-lane layout the next product's B operand wants)
+//                  a lane of the 32x32 result holds, for its column, rows 8 i + 4 (lane / 32) + j; eight
+//                  consecutive result registers are the eight k values of the lane in the next product,
+//                  whose A operand is read from LDS for the same tokens in the same order -- which token
+//                  sits in which k slot does not matter as long as both operands agree)
 // so the query is the lane's column in both results and the online-softmax state (running maximum,
 // denominator, rescale factor) is one scalar per lane.  Scores are kept in the log2 domain.
+#include <type_traits>
+
 #include "xq_internal.h"
 #include "xq_pack_wave.h"
 
 namespace {
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int PF_BM = 128;     // queries per workgroup
 constexpr int PF_BN = 64;      // tokens per key/value tile
-constexpr int PF_KROW = 132;   // halves per K (and row-major V) row in LDS: 128 + 4 of padding
+constexpr int PF_KROW = 136;   // halves per K (and row-major V) row in LDS: 128 + 8 of padding (rows stay 16-byte aligned)
 constexpr int PF_VROW = 68;    // halves per row of the transposed V tile: 64 tokens + 4
 
-template <int G, bool PACK>
+template <int G>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))  // at most 168 registers: three workgroups per CU
 void xq_prefill_kernel(XqPrefillArgs a) {
     constexpr int D = 128;
     __shared__ __attribute__((aligned(16))) _Float16 s_k[PF_BN * PF_KROW];
     __shared__ __attribute__((aligned(16))) _Float16 s_vt[D * PF_VROW];
     static_assert(D * PF_VROW >= PF_BN * PF_KROW, "the row-major V tile of the pack reuses the transposed tile's space");
-    __shared__ float4 s_par[PACK ? PF_BN / G : 1][PACK ? G * (D / G) : 1];   // value-group parameters of the pack
+    __shared__ float4 s_par[PF_BN / G][G * (D / G)];   // value-group parameters of the pack
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int n_qb = (a.T + PF_BM - 1) / PF_BM;
     const int qb = n_qb - 1 - (int)blockIdx.x;   // longest blocks first
@@ -52,7 +57,8 @@ void xq_prefill_kernel(XqPrefillArgs a) {
     // ---- quantize + pack of the block's own 128 tokens (the diagonal tiles of its attention): done by
     // the workgroup of the kv head's first query head, before the attention state takes its registers;
     // the attention loop below finds these tiles in L2
-    if constexpr (PACK) {
+    // (a.Tq = 0 when the caller wants the attention alone: the same kernel, so that the two can be compared)
+    {
         if (hq % rep == 0) {
             _Float16 *s_v = s_vt;   // the pack wants V row-major: same space as the transposed tile of the loop
             for (int t0 = qb * PF_BM; t0 < min(qb * PF_BM + PF_BM, a.Tq); t0 += PF_BN) {   // (uniform over the workgroup)
@@ -97,13 +103,13 @@ void xq_prefill_kernel(XqPrefillArgs a) {
     }
     const int col = lane & 31, g2 = lane >> 5;
     const int tq = qb * PF_BM + wave * 32 + col;          // this lane's query
-    // B operand of S^T = K Q^T: the lane's query row, k-step ks holds channels 8 ks + 4 g2 .. + 3
-    f16x4 qreg[16];
+    // B operand of S^T = K Q^T: the lane's query row, k-step ks holds channels 16 ks + 8 g2 .. + 7
+    f16x8 qreg[8];
     {
         const int tqc = min(tq, a.T - 1);
         const uint16_t *qp = a.q + ((((int64_t)lz * a.batch + bi) * a.n_q_heads + hq) * a.T + tqc) * D;
 #pragma unroll
-        for (int ks = 0; ks < 16; ++ks) qreg[ks] = *(const f16x4 *)(qp + 8 * ks + 4 * g2);
+        for (int ks = 0; ks < 8; ++ks) qreg[ks] = *(const f16x8 *)(qp + 16 * ks + 8 * g2);
     }
     f32x16 oacc[4];   // O^T: block c = channels 32 c .. 32 c + 31 (rows), this lane's query (column)
 #pragma unroll
@@ -112,7 +118,9 @@ void xq_prefill_kernel(XqPrefillArgs a) {
         for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
     const int n_kt = min((qb * PF_BM + PF_BM - 1) / PF_BN + 1, (a.T + PF_BN - 1) / PF_BN);
-    for (int kt = 0; kt < n_kt; ++kt) {
+    // one key/value tile; masked: some (token, query) pair of the workgroup lies above the diagonal
+    auto one_tile = [&](int kt, auto masked_flag) __attribute__((always_inline)) {
+        constexpr bool masked = decltype(masked_flag)::value;
         const int t0 = kt * PF_BN;
         __syncthreads();   // the previous tile's readers are done
         // ---- K tile -> LDS row-major (16 bytes per thread and pass); rows past T are zero
@@ -151,59 +159,67 @@ void xq_prefill_kernel(XqPrefillArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[rb][r] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 16; ++ks) {
-                const f16x4 ka = *(const f16x4 *)&s_k[(32 * rb + col) * PF_KROW + 8 * ks + 4 * g2];
-                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x8f16(ka, qreg[ks], sacc[rb], 0, 0, 0);
+            for (int ks = 0; ks < 8; ++ks) {
+                const f16x8 ka = *(const f16x8 *)&s_k[(32 * rb + col) * PF_KROW + 16 * ks + 8 * g2];
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qreg[ks], sacc[rb], 0, 0, 0);
             }
         }
-        // ---- causal mask, online softmax (log2 domain); result register 4 i + j = token 8 i + 4 g2 + j of the block
+        // ---- causal mask, online softmax (log2 domain; the scale is applied inside the exponent's
+        // multiply-add); result register 4 i + j = token 8 i + 4 g2 + j of the block
         float mx = -INFINITY;
-        const bool diag = t0 + PF_BN - 1 > qb * PF_BM + wave * 32;   // some (token, query) pair of this wave is masked
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float s = sacc[rb][r] * a.scale_log2e;
-                if (diag) {
+                if constexpr (masked) {
                     const int tn = t0 + 32 * rb + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                    s = tn > tq ? -INFINITY : s;
+                    sacc[rb][r] = tn > tq ? -INFINITY : sacc[rb][r];
                 }
-                sacc[rb][r] = s;
-                mx = fmaxf(mx, s);
+                mx = fmaxf(mx, sacc[rb][r]);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);           // finite from the first tile on: token 0 is visible to every query
+        const float m_new = fmaxf(m_run, mx * a.scale_log2e);   // (the scale is positive) finite from the first tile on: token 0 is visible to every query
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         float psum = 0.f;
-        f16x4 pb[2][4];
+        // P^T as the B operand of the second product: its k-step (rb, i) takes the lane's result
+        // registers 8 i .. 8 i + 7 of block rb, i.e. tokens 32 rb + 16 i + 4 g2 + {0..3} and + 8 + {0..3}
+        f16x8 pb[2][2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float p = __builtin_amdgcn_exp2f(sacc[rb][4 * i + j] - m_new);
+                for (int j = 0; j < 8; ++j) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[rb][8 * i + j], a.scale_log2e, -m_new));
                     psum += p;
                     pb[rb][i][j] = (_Float16)p;
                 }
         psum += __shfl_xor(psum, 32, 64);
         l_run = l_run * alpha + psum;
         m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // (wave-uniform: the running maximum of most queries stops moving early)
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+            for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
-        // ---- O^T += V^T P^T: k-step (rb, i) = tokens 32 rb + 8 i .. + 7
+                for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+        }
+        // ---- O^T += V^T P^T: the A operand takes the same tokens, in the same order, from the transposed tile
 #pragma unroll
         for (int c = 0; c < 4; ++c)
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const f16x4 va = *(const f16x4 *)&s_vt[(32 * c + col) * PF_VROW + 32 * rb + 8 * i + 4 * g2];
-                    oacc[c] = __builtin_amdgcn_mfma_f32_32x32x8f16(va, pb[rb][i], oacc[c], 0, 0, 0);
+                for (int i = 0; i < 2; ++i) {
+                    const _Float16 *vp = &s_vt[(32 * c + col) * PF_VROW + 32 * rb + 16 * i + 4 * g2];
+                    const f16x4 lo = *(const f16x4 *)vp, hi = *(const f16x4 *)(vp + 8);
+                    const f16x8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[rb][i], oacc[c], 0, 0, 0);
                 }
-    }
+    };
+    // tiles wholly below the diagonal of every query of the workgroup need no mask
+    const int n_plain = min(n_kt, (qb * PF_BM + 1) / PF_BN);
+    for (int kt = 0; kt < n_plain; ++kt) one_tile(kt, std::false_type{});
+    for (int kt = n_plain; kt < n_kt; ++kt) one_tile(kt, std::true_type{});
     // ---- normalise and store: register 4 i + j of block c = channel 32 c + 8 i + 4 g2 + j of this lane's query
     if (tq < a.T) {
         const float inv = 1.0f / l_run;
@@ -222,10 +238,9 @@ void xq_prefill_kernel(XqPrefillArgs a) {
 hipError_t xq_launch_prefill(const XqPrefillArgs &a, int g, int n_layers, int pack, hipStream_t s) {
     const int n_qb = (a.T + PF_BM - 1) / PF_BM;
     dim3 grid(n_qb, a.batch * a.n_q_heads, n_layers), block(256);
-    if (g == 32 && pack) xq_prefill_kernel<32, true><<<grid, block, 0, s>>>(a);
-    else if (g == 64 && pack) xq_prefill_kernel<64, true><<<grid, block, 0, s>>>(a);
-    else if (g == 32) xq_prefill_kernel<32, false><<<grid, block, 0, s>>>(a);
-    else if (g == 64) xq_prefill_kernel<64, false><<<grid, block, 0, s>>>(a);
+    (void)pack;   // the attention alone is the same kernel with a.Tq = 0
+    if (g == 32) xq_prefill_kernel<32><<<grid, block, 0, s>>>(a);
+    else if (g == 64) xq_prefill_kernel<64><<<grid, block, 0, s>>>(a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -94,6 +94,9 @@ def test_prefill_attention_pack_paged_and_errors(tl):
     with pytest.raises(XqError) as e:        # the layers are no longer empty
         cache.prefill_attention_pack(Q.cuda(), K.cuda(), V.cuda(), sigma)
     assert e.value.code == -4
+    with pytest.raises(XqError) as e:        # the scale must be positive
+        cache.prefill_attention_pack(Q.cuda(), K.cuda(), V.cuda(), -sigma, pack=False)
+    assert e.value.code == -1
     cache.close()
     w64 = synth.scaled(synth.workloads()[0], n_layers=2)
     c64 = tl.make_cache(w64, max_tokens=64)
@@ -135,12 +138,25 @@ def test_prefill_attention_pack_full_size_and_saving(tl):
 
     fused = tl.make_cache(w, max_tokens=T + 2)
     split = tl.make_cache(w, max_tokens=T + 2)
-    fused.prefill_attention_pack(Q, Kd, Vd, sigma, out=out)          # warm-up (clocks, code load)
-    fused.reset()
-    t_fused = timed(lambda: fused.prefill_attention_pack(Q, Kd, Vd, sigma, out=out))
     out_split = torch.empty_like(out)
-    t_attn = timed(lambda: split.prefill_attention_pack(Q, Kd, Vd, sigma, out=out_split, pack=False))
-    t_pack = timed(lambda: split.quantize_pack(Kd, Vd))
+    fused.prefill_attention_pack(Q, Kd, Vd, sigma, out=out)          # warm-up (clocks, code load)
+    tf, ta, tp = [], [], []
+    for r in range(4):                                   # the two routes in turn, in alternating order; medians
+        fused.reset()
+        split.reset()
+
+        def run_fused():
+            tf.append(timed(lambda: fused.prefill_attention_pack(Q, Kd, Vd, sigma, out=out)))
+
+        def run_split():
+            ta.append(timed(lambda: split.prefill_attention_pack(Q, Kd, Vd, sigma, out=out_split, pack=False)))
+            tp.append(timed(lambda: split.quantize_pack(Kd, Vd)))
+
+        for f in ((run_fused, run_split) if r % 2 == 0 else (run_split, run_fused)):
+            f()
+    med = lambda x: float(np.median(x))
+    t_fused, t_attn, t_pack = med(tf), med(ta), med(tp)
+    print("fused runs " + ", ".join(f"{x:.1f}" for x in tf) + "; attention-only runs " + ", ".join(f"{x:.1f}" for x in ta))
     assert torch.equal(out, out_split)
     Tq = fused.length(0)[1]
     used = {"k_codes": Tq * 128 * 2 // 8, "v_codes": Tq * 128 * 2 // 8, "k_meta": Tq // w.group * 128 * 4,
