@@ -112,6 +112,7 @@ struct XqPrefillArgs {
     float *out;          // same shape, fp32
     int32_t T, Tq;       // prompt length; tokens of it that are packed
     int32_t batch, n_q_heads;
+    int32_t n_layers;    // layers of the launch; set by the launcher
     float scale_log2e;   // sm_scale * log2(e)
 };
 hipError_t xq_launch_prefill(const XqPrefillArgs &a, int g, int n_layers, int pack, hipStream_t s);

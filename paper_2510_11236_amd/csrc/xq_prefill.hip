@@ -47,10 +47,19 @@ void xq_prefill_kernel(XqPrefillArgs a) {
     static_assert(D * PF_VROW >= PF_BN * PF_KROW, "the row-major V tile of the pack reuses the transposed tile's space");
     __shared__ float4 s_par[PF_BN / G][G * (D / G)];   // value-group parameters of the pack
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    // Workgroups are dealt round-robin to the 8 XCDs by linear id, and each XCD has its own L2: all
+    // workgroups of a kv head (its query blocks, longest first, and the query heads that share it,
+    // side by side) get ids that are equal mod 8, so that one L2 sees a head's K/V tiles and the
+    // workgroups of a head that run together walk them together.  (With query blocks along the grid's
+    // fastest dimension every XCD fetched every head's tiles: 157 GB of HBM traffic at the 32k shape.)
     const int n_qb = (a.T + PF_BM - 1) / PF_BM;
-    const int qb = n_qb - 1 - (int)blockIdx.x;   // longest blocks first
-    const int hq = blockIdx.y % a.n_q_heads, bi = blockIdx.y / a.n_q_heads, lz = blockIdx.z;
-    const int rep = a.n_q_heads / a.pk.n_kv_heads, hkv = hq / rep;
+    const int rep = a.n_q_heads / a.pk.n_kv_heads, n_kvh = a.n_layers * a.batch * a.pk.n_kv_heads;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per_kv = n_qb * rep;
+    const int kvidx = (slot / per_kv) * 8 + xcd;
+    if (kvidx >= n_kvh) return;   // (the grid is padded to a multiple of 8 kv heads)
+    const int qb = n_qb - 1 - (slot % per_kv) / rep;   // longest blocks first
+    const int hkv = kvidx % a.pk.n_kv_heads, bi = (kvidx / a.pk.n_kv_heads) % a.batch, lz = kvidx / (a.pk.n_kv_heads * a.batch);
+    const int hq = hkv * rep + (slot % per_kv) % rep;
     const uint16_t *kg = a.pk.k_src + lz * a.pk.s_layer + bi * a.pk.s_batch + hkv * a.pk.s_head;
     const uint16_t *vg = a.pk.v_src + lz * a.pk.s_layer + bi * a.pk.s_batch + hkv * a.pk.s_head;
     const XqLayerDesc dsc = a.pk.layers[a.pk.layer0 + lz];
@@ -237,10 +246,13 @@ void xq_prefill_kernel(XqPrefillArgs a) {
 
 hipError_t xq_launch_prefill(const XqPrefillArgs &a, int g, int n_layers, int pack, hipStream_t s) {
     const int n_qb = (a.T + PF_BM - 1) / PF_BM;
-    dim3 grid(n_qb, a.batch * a.n_q_heads, n_layers), block(256);
+    const int rep = a.n_q_heads / a.pk.n_kv_heads, n_kvh = n_layers * a.batch * a.pk.n_kv_heads;
+    XqPrefillArgs b = a;
+    b.n_layers = n_layers;
+    dim3 grid((unsigned)(8 * ((n_kvh + 7) / 8) * n_qb * rep)), block(256);
     (void)pack;   // the attention alone is the same kernel with a.Tq = 0
-    if (g == 32) xq_prefill_kernel<32><<<grid, block, 0, s>>>(a);
-    else if (g == 64) xq_prefill_kernel<64><<<grid, block, 0, s>>>(a);
+    if (g == 32) xq_prefill_kernel<32><<<grid, block, 0, s>>>(b);
+    else if (g == 64) xq_prefill_kernel<64><<<grid, block, 0, s>>>(b);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
