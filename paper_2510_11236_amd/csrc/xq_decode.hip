@@ -1204,11 +1204,13 @@ void xq_decode_kernel(XqDecodeArgs a) {
     // others simply leave.  The counter is back at zero for the next launch.
     // Ordering without cache-wide write-backs or invalidations (a device-scope fence costs an L2
     // sweep per workgroup here and halves the kernel's speed): the partials are device-scope
-    // stores, the barrier below waits until the memory system has acknowledged every one of them
-    // (s_waitcnt vmcnt(0) before s_barrier), only then does thread 0 count the workgroup in with a
-    // device-scope atomic; the last arrival's loads are device-scope loads issued after its own
-    // atomic has returned.
+    // (write-through) stores; every thread waits until the memory system has acknowledged its own
+    // (the wait is spelled out: a workgroup barrier by itself does not wait for stores, whose
+    // visibility inside a workgroup needs no acknowledgement); after the barrier thread 0 counts the
+    // workgroup in with a device-scope atomic; the last arrival's loads are device-scope loads issued
+    // after its own atomic has returned.
     __shared__ uint32_t s_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     uint32_t *arrive = a.arrivals + (int64_t)lz * nbh + bh;
     if (tid == 0) s_last = __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)a.n_splits;
