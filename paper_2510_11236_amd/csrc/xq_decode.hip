@@ -1223,7 +1223,7 @@ void xq_decode_kernel(XqDecodeArgs a) {
             return ((int64_t)(lz * NLAY + y) * a.batch + bi) * a.n_q_heads + hkv * a.rep + a.q_head0 + n;
         },
         a.ws, a.out, a.n_splits + 1, (float *)s_raw, tid);
-    if (tid == 0) *arrive = 0;
+    if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // (written through, like the counts)
 }
 
 template <int NREP>
