@@ -303,13 +303,13 @@ def main():
     # how a real decoder must call it: one call per layer (layer l+1's query needs layer l's output)
     # eagerly, and as one HIP graph of the same calls replayed (the library only enqueues kernels, so a
     # capture records them; a replay takes the host's launch cost out of the figure)
-    def time_per_layer_calls(n=5):
+    def time_per_layer_calls(n=10):
         def once():
             for l in range(w.n_layers):
                 cache.decode_attention(qs[0][l:l + 1], sigma, out=out[l:l + 1], layer0=l, flags=alu)
 
         def timed(fn):
-            for _ in range(2):
+            for _ in range(6):       # (the first replays of a fresh graph are slow: its upload, the clock)
                 fn()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
