@@ -220,8 +220,8 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * merge launch that follows the decode launch, or the decode launch itself: the workgroups of a
  * (layer, sequence, kv head) count themselves in on a counter in the cache's arena and the last to
  * arrive merges.  Both sum in the same fixed order: same results bit for bit.  By default the library
- * chooses (the decode launch merges when it is brief: a single round of workgroups of at most 8 tiles,
- * as in a call for one layer of a short cache, where a second launch's fixed cost shows).
+ * chooses (the decode launch merges when its workgroups run in about one round, as in a call for one
+ * layer, where a second launch's fixed cost shows; a call over many layers gets the merge launch).
  * XQ_DECODE_MERGE_LAUNCH forces the merge launch, XQ_DECODE_MERGE_IN_LAUNCH the other (both:
  * XQ_ERR_INVALID_ARG).  Because of the counters, two decode calls on one cache that may merge in the
  * decode launch must not overlap in time on the GPU (calls on one stream never do); calls with

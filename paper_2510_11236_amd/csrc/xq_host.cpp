@@ -793,7 +793,7 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
     struct Run {
         int l, e, fused;
         int n_splits, tps;  // each run is a launch of its own and gets its own split plan
-        bool brief;         // one round of workgroups of at most 8 tiles each: a launch of a few microseconds
+        bool brief;         // (about) one round of workgroups: a launch whose tail a merge launch would lengthen
         int64_t ws_off;     // where its partials start in the workspace, in floats
     };
     Run runs[XQ_MAX_LAYERS];
@@ -829,7 +829,7 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
                                                                 r.fused != 0, c.group, cache->layers[r.l].bk,
                                                                 cache->layers[r.l].bv));
         plan_splits(cache, Tq, work_items, 256 * wgs_per_cu, &r.n_splits, &r.tps);
-        r.brief = r.tps <= 8 && work_items * (r.n_splits + 1) <= 256 * wgs_per_cu;
+        r.brief = work_items * (r.n_splits + 1) <= 256 * wgs_per_cu * 5 / 4;
         r.ws_off = ws_floats;
         ws_floats += (int64_t)workspace_floats(c, r.e - r.l, r.n_splits);
     }
@@ -871,9 +871,9 @@ static int decode_impl(const xq_cache *cache, int32_t layer0, int32_t n_layers, 
         a.pair_order = (a.reuse_codes && l % group_size(c) == 0 && (e - l) % group_size(c) == 0) ? group_size(c) : 0;
         a.rep = rep;
         // Who merges the split partials: the last workgroup to arrive, or a launch of its own.  Measured,
-        // the first wins only where a second launch's fixed cost shows (one layer of a 4k-token cache:
-        // 12.9 against 13.4 us per call); on long launches its round trips to memory at the tail cost as
-        // much as the launch they save (one layer of the 32k GQA cache: 3 % slower).
+        // the first wins where a second launch's fixed cost shows -- calls for one layer: 12.7 against
+        // 13.5 us on a 4k cache, 75.5 against 76.5 us on the 32k one -- and loses where the decode launch
+        // runs many rounds of workgroups anyway (32 layers of the 4k cache in one call: 82 against 77 us).
         const bool in_launch = (flags & XQ_DECODE_MERGE_IN_LAUNCH) || (!(flags & XQ_DECODE_MERGE_LAUNCH) && runs[ri].brief);
         a.arrivals = in_launch ? cache->arrivals : nullptr;
         for (int i = 0; i < n_parts; ++i) {
