@@ -225,7 +225,9 @@ int xq_append_token(xq_cache *cache, int32_t layer0, int32_t n_layers, const voi
  * XQ_DECODE_MERGE_LAUNCH forces the merge launch, XQ_DECODE_MERGE_IN_LAUNCH the other (both:
  * XQ_ERR_INVALID_ARG).  Because of the counters, two decode calls on one cache that may merge in the
  * decode launch must not overlap in time on the GPU (calls on one stream never do); calls with
- * XQ_DECODE_MERGE_LAUNCH touch no counter and may overlap when their workspaces differ. */
+ * XQ_DECODE_MERGE_LAUNCH touch no counter and may overlap when their workspaces differ.  The counters
+ * are zero whenever no decode launch is running; after an XQ_ERR_HIP from a decode call that is no
+ * longer certain: create the cache anew (xq_cache_create clears them). */
 #define XQ_DECODE_MERGE_LAUNCH 8
 #define XQ_DECODE_MERGE_IN_LAUNCH 16
 int xq_decode_attention(const xq_cache *cache, int32_t layer0, int32_t n_layers, const void *q_f16,
