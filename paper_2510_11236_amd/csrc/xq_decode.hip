@@ -1091,29 +1091,32 @@ void xq_decode_kernel(XqDecodeArgs a) {
                 acr[v][c] = 0.f;
             }
         const int r = seqT - seqTq;
-        // the rows of the row's next token are fetched while the current one is worked on: with one
-        // workgroup per ring the walk is a chain of memory latencies otherwise, and in a call for one
-        // layer of a short cache the ring workgroup is the last to finish
-        uint32_t kn[NLAY][CR / 2], vn[NLAY][CR / 2];
-        auto ring_load = [&](int i) {
+        // The rows of the row's next two tokens are in flight while the current one is worked on: with one
+        // workgroup per ring the walk is a chain of memory latencies otherwise (in a call for one layer
+        // of a short cache the ring workgroup is the last to finish), and two tokens per row keep
+        // about as many bytes in flight per CU as the packed-token workgroups do.
+        uint32_t kn[2][NLAY][CR / 2], vn[2][NLAY][CR / 2];
+        auto ring_load = [&](int i, auto buf) {
+            constexpr int b = decltype(buf)::value;
             const int slot = (seqTq + min(i, r - 1)) % a.R;   // (past the end: the last token again, not used)
 #pragma unroll
             for (int y = 0; y < NLAY; ++y) {
-                VecLoad<CR / 2>::ld((const uint32_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2, kn[y]);
-                VecLoad<CR / 2>::ld((const uint32_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2, vn[y]);
+                VecLoad<CR / 2>::ld((const uint32_t *)(a.arena + dsc[y].k_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2, kn[b][y]);
+                VecLoad<CR / 2>::ld((const uint32_t *)(a.arena + dsc[y].v_res + (int64_t)bh * a.st.res) + (slot * D + r16 * CR) / 2, vn[b][y]);
             }
         };
-        if (r > 0) ring_load(wave * 4 + row);
-        for (int i = wave * 4 + row; i < r; i += 16) {
+        // one ring token from buffer b; its buffer is refilled with token i + 32 as soon as it is copied out
+        auto ring_token = [&](int i, auto buf) {
+            constexpr int b = decltype(buf)::value;
 #pragma unroll
             for (int y = 0; y < NLAY; ++y) {
                 uint32_t kw[CR / 2], vw[CR / 2];
 #pragma unroll
                 for (int c = 0; c < CR / 2; ++c) {
-                    kw[c] = kn[y][c];
-                    vw[c] = vn[y][c];
+                    kw[c] = kn[b][y][c];
+                    vw[c] = vn[b][y][c];
                 }
-                if (y == NLAY - 1) ring_load(i + 16);
+                if (y == NLAY - 1) ring_load(i + 32, buf);
                 float kf[CR], vf[CR];
 #pragma unroll
                 for (int c = 0; c < CR; ++c) {
@@ -1136,6 +1139,15 @@ void xq_decode_kernel(XqDecodeArgs a) {
                     m_run[v] = m_new;
                 }
             }
+        };
+        const int i_first = wave * 4 + row;
+        if (r > 0) {
+            ring_load(i_first, std::integral_constant<int, 0>{});
+            ring_load(i_first + 16, std::integral_constant<int, 1>{});
+        }
+        for (int i = i_first; i < r; i += 32) {
+            ring_token(i, std::integral_constant<int, 0>{});
+            if (i + 16 < r) ring_token(i + 16, std::integral_constant<int, 1>{});
         }
         // merge the 4 rows of the wave
 #pragma unroll
