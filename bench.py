@@ -284,6 +284,10 @@ def main():
              "algorithmic_frac": ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         tb = prof.get(f"{w.name}:{name}{fam}")
         e["traffic_frac"] = tb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS if tb else None
+        # the 70 % target of the 32k configurations, for this family and schedule (same rule as roofline.target_met)
+        consumed = algorithmic_bytes(w, T0, fused=False) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+        e["consumed_frac"] = consumed
+        e["target_met"] = (max(e["algorithmic_frac"], consumed) >= HBM_TARGET_FRAC) if T0 >= 32768 else None
         return e
 
     by_schedule = {name: sched_entry(name, ms, fam_key) for name, ms in probe.items()}
