@@ -287,7 +287,8 @@ def main():
         # the 70 % target of the 32k configurations, for this family and schedule (same rule as roofline.target_met)
         consumed = algorithmic_bytes(w, T0, fused=False) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
         e["consumed_frac"] = consumed
-        e["target_met"] = (max(e["algorithmic_frac"], consumed) >= HBM_TARGET_FRAC) if T0 >= 32768 else None
+        e["target_met"] = (e["algorithmic_frac"] >= HBM_TARGET_FRAC) if T0 >= 32768 else None
+        e["target_met_on_consumed_bytes"] = (consumed >= HBM_TARGET_FRAC) if T0 >= 32768 else None
         return e
 
     by_schedule = {name: sched_entry(name, ms, fam_key) for name, ms in probe.items()}
@@ -397,10 +398,12 @@ def main():
                      "algorithmic_bytes_per_launch": alg, "decode_ms": decode_ms,
                      "consumed_bytes_per_launch": consumed, "consumed_frac": consumed_frac,
                      "target_frac": HBM_TARGET_FRAC if T0 >= 32768 else None,
-                     "target_met": (max(achieved / HBM_PEAK_GBPS, consumed_frac) >= HBM_TARGET_FRAC) if T0 >= 32768 else None,
-                     "target_basis": "frac prices the HBM bytes the timed schedule must fetch (shared codes once per fused pair); "
-                                     "consumed_frac prices the bytes its layers consume (shared codes once per layer that reads "
-                                     "them: step time <= those bytes / 0.70 / 8 TB/s); the target counts as met when either is >= 0.70"},
+                     "target_met": (achieved / HBM_PEAK_GBPS >= HBM_TARGET_FRAC) if T0 >= 32768 else None,
+                     "target_met_on_consumed_bytes": (consumed_frac >= HBM_TARGET_FRAC) if T0 >= 32768 else None,
+                     "target_basis": "target_met: frac >= 0.70, frac pricing the HBM bytes the timed schedule must fetch (shared codes "
+                                     "once per fused pair). target_met_on_consumed_bytes: the looser reading, consumed_frac >= 0.70, "
+                                     "pricing the bytes the layers consume (shared codes once per layer that reads them), i.e. "
+                                     "step time <= those bytes / 0.70 / 8 TB/s; it can exceed 1 for a fused schedule"},
         "token_head_layers_per_s": w.n_layers * w.batch * w.n_kv_heads * T_mid / (ms_per_step * 1e-3),
         "decode_only_by_schedule": by_schedule,
         "decode_only_by_family": by_family,
